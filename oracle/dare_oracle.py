@@ -1,0 +1,217 @@
+"""CPU oracle for one DARE attention-layer step.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain reference that the parity tests, the smoke test
+and the benchmark's ``cpu_baseline`` leg compare the HIP library against.  The
+product path never imports it, and it imports nothing from the product.
+
+Everything is numpy in float64.  Inputs may arrive in any float dtype and are
+widened exactly.  Nothing here is blocked, fused or reordered: each function
+is the paper's definition or the paper's algorithm written out step by step.
+
+What the layer computes (paper Sec. 3, Alg. 1 "DARE-KV", Alg. 2 "DARE-O",
+App. E.1/E.2):
+
+  dense       Q = X Wq, K = X Wk, V = X Wv, per head softmax(Q K^T / sqrt(Dh)) V,
+              concatenated heads times Wo                          (App. E.2)
+  drift score s_i = 1 - <q_i, p_i> / (|q_i| |p_i|), q_i = head 0 of the query of
+              token i at this step, p_i = the same at the previous step
+                                                    (Sec. 3.1 eq. 1, Sec. 3.2)
+  reuse set   R = {i : s_i <= tau}, refreshed set = complement   (Sec. 3.2 eq. 2)
+  DARE-KV     K, V rows of the refreshed set are recomputed, rows of R keep the
+              cached values; attention and Wo over all rows             (Alg. 1)
+  DARE-O      K, V dense; attention (and, since the cache holds the layer
+              output, Wo) only for the refreshed rows, rows of R return the
+              cached output                        (Alg. 2, App. E.1 second form)
+  both        hybrid K/V cache and refreshed-row-only attention at once.
+
+Readings taken where the paper is silent or has two forms:
+  * weights are [d_in, d_out], Y = X W                   (Sec. 3.2 eq. 3, App. E.1)
+  * softmax scale is 1/sqrt(head_dim) per head (App. E writes the one-head form)
+  * the score uses the cosine form of Sec. 3.1 on head 0 = output columns
+    [0, head_dim) of Wq; score_head = -1 scores the whole query vector
+  * the previous query is the previous *step's* query: it is replaced for
+    every token at every step, whatever the mode
+  * the output cache holds rows *after* Wo (App. E.1); ``step_o_prewo`` below is
+    the literal Alg. 2 (cache before Wo) and is used only to test that both
+    readings are the same function
+  * the threshold test is taken on the score rounded to float32 against the
+    float32 threshold (the precision the kernels decide in); NaN scores refresh
+  * a zero-norm query gives cosine 0 (denominator floored at 1e-30)
+  * a dense or DARE-O step writes the dense K, V into the K/V caches, so a later
+    DARE-KV step starts from valid rows
+  * index lists are ascending flat token ids b*T + i.
+
+Parity pinning: every function here is pinned by tests/test_oracle_pins.py
+(brute force in Python loops, closed forms, invariants).  The paper prints no
+worked numeric example, so there is no golden fixture from the paper.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+MODE_DENSE = 0
+MODE_KV = 1
+MODE_O = 2
+MODE_KVO = 3
+
+_DENOM_FLOOR = 1e-30
+
+
+def _f64(a):
+    return np.asarray(a, dtype=np.float64)
+
+
+def drift_scores(q, p):
+    """Sec. 3.1 eq. 1: s = 1 - cos(q, p), row by row.  q, p: [..., n]."""
+    q = _f64(q)
+    p = _f64(p)
+    dot = np.sum(q * p, axis=-1)
+    nq = np.sum(q * q, axis=-1)
+    npp = np.sum(p * p, axis=-1)
+    den = np.maximum(np.sqrt(nq * npp), _DENOM_FLOOR)
+    return 1.0 - dot / den
+
+
+def reuse_decision(scores, tau):
+    """Sec. 3.2 eq. 2: reuse iff s <= tau, decided in float32.  NaN -> refresh."""
+    s32 = np.asarray(scores, dtype=np.float64).astype(np.float32)
+    t32 = np.float32(tau)
+    with np.errstate(invalid="ignore"):
+        return s32 <= t32
+
+
+def selection(reuse):
+    """Ascending flat ids of refreshed tokens, per-sequence counts and offsets.
+
+    reuse: bool [B, T].  Returns (sel_idx int32 [n], sel_count int32 [B],
+    sel_off int32 [B+1])."""
+    reuse = np.asarray(reuse, dtype=bool)
+    B, T = reuse.shape
+    sel_idx = np.flatnonzero(~reuse.reshape(-1)).astype(np.int32)
+    sel_count = (~reuse).sum(axis=1).astype(np.int32)
+    sel_off = np.zeros(B + 1, dtype=np.int32)
+    sel_off[1:] = np.cumsum(sel_count)
+    return sel_idx, sel_count, sel_off
+
+
+def attention_rows(q, k, v, n_heads):
+    """App. E.2: bidirectional softmax attention of query rows q [n, d] against
+    all keys/values k, v [T, d] of one sequence, head by head."""
+    q = _f64(q)
+    k = _f64(k)
+    v = _f64(v)
+    n, d = q.shape
+    dh = d // n_heads
+    out = np.empty((n, d), dtype=np.float64)
+    for h in range(n_heads):
+        c = slice(h * dh, (h + 1) * dh)
+        z = (q[:, c] @ k[:, c].T) / np.sqrt(float(dh))
+        m = np.max(z, axis=1, keepdims=True)
+        w = np.exp(z - m)
+        out[:, c] = (w @ v[:, c]) / np.sum(w, axis=1, keepdims=True)
+    return out
+
+
+def dense_layer(x, wq, wk, wv, wo, n_heads):
+    """App. E.2 for a batch: x [B, T, d] -> (out, Q, K, V), all [B, T, d]."""
+    x = _f64(x)
+    wq, wk, wv, wo = _f64(wq), _f64(wk), _f64(wv), _f64(wo)
+    Q = x @ wq
+    K = x @ wk
+    V = x @ wv
+    out = np.empty_like(Q)
+    for b in range(x.shape[0]):
+        out[b] = attention_rows(Q[b], K[b], V[b], n_heads) @ wo
+    return out, Q, K, V
+
+
+def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
+               n_heads, score_head=0):
+    """One step of the layer in mode DENSE / KV (Alg. 1) / O (Alg. 2) / KVO.
+
+    x [B,T,d]; w* [d,d]; q_prev [B,T,Dh] (or [B,T,d] when score_head = -1);
+    k_cache, v_cache, o_cache [B,T,d] hold the previous step's state.
+    Returns a dict with out, k_cache, v_cache, o_cache, q_prev (all updated,
+    float64), scores [B,T] float64, reuse_mask uint8 [B,T] (1 = reused),
+    sel_idx, sel_count, sel_off.
+    """
+    if mode not in (MODE_DENSE, MODE_KV, MODE_O, MODE_KVO):
+        raise ValueError("unknown mode")
+    x = _f64(x)
+    wq, wk, wv, wo = _f64(wq), _f64(wk), _f64(wv), _f64(wo)
+    B, T, d = x.shape
+    dh = d // n_heads
+
+    # Alg. 1/2 line 2: the query of every token.
+    Q = x @ wq
+
+    # Alg. 1/2 line 3: drift of head 0 against the previous step's head 0.
+    q_sc = Q if score_head < 0 else Q[:, :, score_head * dh:(score_head + 1) * dh]
+    scores = drift_scores(q_sc, _f64(q_prev))
+
+    # Alg. 1/2 lines 4-5.
+    if mode == MODE_DENSE:
+        reuse = np.zeros((B, T), dtype=bool)
+    else:
+        reuse = reuse_decision(scores, tau)
+    sel_idx, sel_count, sel_off = selection(reuse)
+
+    # Keys and values.
+    if mode in (MODE_KV, MODE_KVO):
+        # Alg. 1 lines 6-9: refresh the selected rows, keep the cached ones.
+        K = _f64(k_cache).copy()
+        V = _f64(v_cache).copy()
+        for b in range(B):
+            rows = np.flatnonzero(~reuse[b])
+            K[b, rows] = x[b, rows] @ wk
+            V[b, rows] = x[b, rows] @ wv
+    else:
+        # Alg. 2 line 7 / App. E.2.
+        K = x @ wk
+        V = x @ wv
+
+    # Attention and output projection.
+    if mode in (MODE_O, MODE_KVO):
+        # Alg. 2 lines 6, 8-11 with the cache holding rows after Wo.
+        out = _f64(o_cache).copy()
+        for b in range(B):
+            rows = np.flatnonzero(~reuse[b])
+            out[b, rows] = attention_rows(Q[b, rows], K[b], V[b], n_heads) @ wo
+    else:
+        # Alg. 1 lines 10-11.
+        out = np.empty((B, T, d), dtype=np.float64)
+        for b in range(B):
+            out[b] = attention_rows(Q[b], K[b], V[b], n_heads) @ wo
+
+    return {
+        "out": out,
+        "k_cache": K,
+        "v_cache": V,
+        "o_cache": out.copy(),
+        "q_prev": q_sc.copy(),
+        "scores": scores,
+        "reuse_mask": reuse.astype(np.uint8),
+        "sel_idx": sel_idx,
+        "sel_count": sel_count,
+        "sel_off": sel_off,
+    }
+
+
+def step_o_prewo(tau, x, wq, wk, wv, wo, q_prev, attn_cache, n_heads,
+                 score_head=0):
+    """Alg. 2 exactly as listed: the cache holds attention rows *before* Wo and
+    Wo multiplies every row.  Returns (out, new attn cache, reuse mask)."""
+    x = _f64(x)
+    wq, wk, wv, wo = _f64(wq), _f64(wk), _f64(wv), _f64(wo)
+    B, T, d = x.shape
+    dh = d // n_heads
+    Q = x @ wq
+    q_sc = Q if score_head < 0 else Q[:, :, score_head * dh:(score_head + 1) * dh]
+    reuse = reuse_decision(drift_scores(q_sc, _f64(q_prev)), tau)
+    K = x @ wk
+    V = x @ wv
+    attn = _f64(attn_cache).copy()
+    for b in range(B):
+        rows = np.flatnonzero(~reuse[b])
+        attn[b, rows] = attention_rows(Q[b, rows], K[b], V[b], n_heads)
+    return attn @ wo, attn, reuse.astype(np.uint8)
