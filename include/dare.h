@@ -1,0 +1,130 @@
+/*
+ * libdare: one bidirectional self-attention layer of a diffusion LLM at one
+ * denoising step with token-wise activation reuse (DARE), for AMD MI355X
+ * (gfx950).  Plain C ABI: pointers and sizes only.
+ *
+ * What a step computes (paper Sec. 3; Alg. 1 "DARE-KV"; Alg. 2 "DARE-O";
+ * App. E.1/E.2):
+ *   Q = X Wq.  For every token i the drift score
+ *       s_i = 1 - <q_i, p_i> / (|q_i| |p_i|)                (Sec. 3.1 eq. 1)
+ *   of its head-0 query q_i against the head-0 query p_i of the previous step
+ *   (Sec. 3.2).  Tokens with s_i <= threshold are reused, the others are
+ *   refreshed (Sec. 3.2 eq. 2).
+ *   DARE_MODE_KV   K and V rows are projected only for the refreshed tokens and
+ *                  written into the K/V caches; attention and Wo over all rows
+ *                  (Alg. 1).
+ *   DARE_MODE_O    K and V for all rows; attention and Wo only for the
+ *                  refreshed rows; reused rows return the cached layer output
+ *                  (Alg. 2, with the cache holding rows after Wo as in App. E.1).
+ *   DARE_MODE_KVO  both at once.
+ *   DARE_MODE_DENSE no reuse: softmax(Q K^T / sqrt(head_dim)) V Wo (App. E.2);
+ *                  also the step that fills the caches.
+ *
+ * Every data pointer below is DEVICE memory owned by the caller unless it says
+ * "host".  Calls are asynchronous on the given HIP stream and never
+ * synchronise.  No exception crosses this boundary: every failure is a status
+ * code, and dare_last_error() gives the text.  Argument errors are detected
+ * before anything is enqueued, so they leave all buffers untouched.
+ * One context serves one stream at a time (it owns scratch memory).
+ */
+#ifndef DARE_H
+#define DARE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dare_ctx dare_ctx;
+
+typedef enum {
+  DARE_OK = 0,
+  DARE_ERR_INVALID_ARG = 1, /* null pointer, bad mode, shape out of range, NaN */
+  DARE_ERR_UNSUPPORTED = 2, /* a shape the kernels are not built for          */
+  DARE_ERR_OOM = 3,         /* device allocation failed                       */
+  DARE_ERR_HIP = 4          /* any other HIP runtime error                    */
+} dare_status;
+
+typedef enum { DARE_F32 = 0, DARE_BF16 = 1 } dare_dtype;
+
+enum { DARE_MODE_DENSE = 0, DARE_MODE_KV = 1, DARE_MODE_O = 2, DARE_MODE_KVO = 3 };
+
+typedef struct {
+  uint32_t struct_size; /* = sizeof(dare_config); anything else is INVALID_ARG  */
+  int32_t hidden;       /* d; must equal n_heads * head_dim                     */
+  int32_t n_heads;
+  int32_t head_dim;     /* 64 or 128                                            */
+  int32_t max_batch;    /* scratch is sized for max_batch * max_seq tokens      */
+  int32_t max_seq;
+  int32_t dtype;        /* DARE_F32: fp32 storage and arithmetic (debug path);
+                           DARE_BF16: bf16 storage, fp32 accumulation           */
+  int32_t score_head;   /* head whose query is scored: 0 = the paper's choice
+                           (Sec. 3.2); -1 = the whole query vector (Sec. 3.1)   */
+  int32_t device;       /* HIP device ordinal                                   */
+  uint32_t flags;       /* reserved, must be 0                                  */
+} dare_config;
+
+/*
+ * Create a context.  wq, wk, wv, wo: device pointers to row-major
+ * [hidden, hidden] matrices of cfg->dtype laid out [d_in, d_out], so that
+ * Y = X W (Sec. 3.2 eq. 3, App. E.1).  They are copied and re-packed inside the
+ * call; the caller may free them after the call returns (the call synchronises
+ * the stream once, it is the only call that does).
+ * Errors: INVALID_ARG (null pointer, bad config), UNSUPPORTED (head_dim not 64
+ * or 128, hidden not a multiple of 64), OOM, HIP.  On error *out_ctx is NULL.
+ */
+dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk,
+                        const void* wv, const void* wo, void* hip_stream,
+                        dare_ctx** out_ctx);
+
+/*
+ * One step of the layer (Alg. 1 / Alg. 2 / App. E.2 depending on mode).
+ *
+ *   hidden     in     [batch, seq, hidden] dtype; already normalised (line 1 of
+ *                     both algorithms is the caller's)
+ *   q_prev     in/out [batch, seq, head_dim] fp32 (or [batch, seq, hidden] when
+ *                     score_head = -1): the scored query of the previous step;
+ *                     replaced by this step's for EVERY token, in every mode
+ *   k_cache    in/out [batch, seq, hidden] dtype.  KV, KVO: refreshed rows are
+ *   v_cache           overwritten, reused rows are read.  DENSE, O: all rows
+ *                     are written.
+ *   o_cache    in/out [batch, seq, hidden] dtype: the layer output of the
+ *                     previous step (after Wo).  O, KVO: reused rows are read.
+ *                     Every mode leaves this step's layer output in it.
+ *   out        out    [batch, seq, hidden] dtype: this step's layer output.  May
+ *                     be the same pointer as o_cache (then no copy is made);
+ *                     partial overlap is an error the call cannot detect.
+ *   reuse_mask out    [batch, seq] bytes, 1 = reused, 0 = refreshed (all 0 in
+ *                     DENSE)
+ *   sel_idx    out, optional (NULL to skip) [batch*seq] int32: ascending flat
+ *                     token ids b*seq+i of the refreshed tokens; entries past
+ *                     the total count are left as they were
+ *   sel_count  out, optional [batch] int32: refreshed tokens per sequence
+ *   scores     out, optional [batch, seq] fp32 drift scores
+ *   threshold  compared in fp32, reuse iff score <= threshold; ignored in DENSE.
+ *              A NaN score refreshes.  NaN threshold is INVALID_ARG.
+ *
+ * Errors: INVALID_ARG (null required pointer, unknown mode, batch or seq < 1,
+ * batch > max_batch, seq > max_seq, NaN threshold), HIP (a launch failed).
+ */
+dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
+                            int seq, const void* hidden, float* q_prev,
+                            void* k_cache, void* v_cache, void* o_cache,
+                            void* out, uint8_t* reuse_mask, int32_t* sel_idx,
+                            int32_t* sel_count, float* scores, void* hip_stream);
+
+/* Free a context and its device memory.  NULL is a no-op. */
+dare_status dare_destroy(dare_ctx* ctx);
+
+/* Text of the last error on this context (or of the last failed dare_create
+ * on this thread when ctx is NULL).  Host pointer, valid until the next call. */
+const char* dare_last_error(const dare_ctx* ctx);
+
+/* Library version, "major.minor".  Host pointer, static. */
+const char* dare_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DARE_H */

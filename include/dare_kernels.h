@@ -1,0 +1,104 @@
+/*
+ * Kernel-level entry points of libdare: each one enqueues a single stage of the
+ * layer step of dare.h on a HIP stream.  dare_layer_step() is built from exactly
+ * these stages; they are exported so that each can be checked against its
+ * definition and timed on its own.  All data pointers are DEVICE memory owned by
+ * the caller; calls are asynchronous and never synchronise.  dtype is a
+ * dare_dtype.  Argument errors return DARE_ERR_INVALID_ARG / UNSUPPORTED before
+ * anything is enqueued.
+ */
+#ifndef DARE_KERNELS_H
+#define DARE_KERNELS_H
+
+#include <stdint.h>
+#include "dare.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Re-pack a projection weight: wt[n, k] = w[k, n] (w is [rows_k, cols_n]
+ * row-major, the Y = X W orientation of Sec. 3.2 eq. 3; wt is [cols_n, rows_k]
+ * row-major with leading dimension ldwt >= rows_k).  The GEMM below consumes wt.
+ */
+dare_status dare_k_pack_weight(int dtype, const void* w, int rows_k, int cols_n,
+                               void* wt, int ldwt, void* hip_stream);
+
+/*
+ * Row-selected projection (Alg. 1 lines 6-7 and 11; Alg. 2 lines 2, 7, 11):
+ *     C[t, 0:n] = A[t, 0:k] . W          for t in rows
+ * rows = idx[0 .. m) when idx != NULL (flat token ids; the same id addresses the
+ * row of A that is read and the row of C that is written), else 0 .. m-1.
+ * m = *m_dev (a device int32, read by the kernel) when m_dev != NULL, else m_max;
+ * m_max bounds the launch and must be >= *m_dev.
+ *   a    [*, lda] dtype, k contiguous          wt [n, k] dtype (packed weight)
+ *   c    column segment s = col / seg_n goes to c[s] (up to 3 segments, each
+ *        [*, ldc] dtype); seg_n must divide n; unused entries NULL
+ *   c32  optional fp32 copy [*, c32_cols] (leading dimension c32_cols) of output
+ *        columns [0, c32_cols), taken from the fp32 accumulators before rounding
+ *        to dtype: the input of the drift score.  c may be all NULL when only
+ *        c32 is wanted (then n == c32_cols).
+ * k must be a multiple of 64, n of 64 (bf16) / 16 (fp32).
+ */
+dare_status dare_k_gemm(int dtype, const void* a, int lda, const void* wt, int n,
+                        int k, int m_max, const int32_t* idx,
+                        const int32_t* m_dev, void* const* c, int ldc, int seg_n,
+                        float* c32, int c32_cols, void* hip_stream);
+
+/*
+ * Drift score and reuse decision (Sec. 3.1 eq. 1, Sec. 3.2 eq. 2; Alg. 1/2
+ * lines 3-5) for n_tokens tokens:
+ *   s = 1 - <q, p> / max(sqrt(|q|^2 |p|^2), 1e-30), q = q_new[t, 0:width],
+ *   p = q_prev[t, 0:width]; mask = (s <= threshold) unless force_refresh;
+ *   then q_prev[t] = q_new[t].
+ *   q_new [n_tokens, ld_new] fp32; q_prev [n_tokens, width] fp32 in/out;
+ *   scores optional [n_tokens] fp32; mask [n_tokens] bytes.
+ */
+dare_status dare_k_score(const float* q_new, int ld_new, int width, float* q_prev,
+                         int n_tokens, float threshold, int force_refresh,
+                         float* scores, uint8_t* mask, void* hip_stream);
+
+/*
+ * Ordered compaction of the refreshed set (Alg. 1/2 line 5): sel_idx = ascending
+ * flat ids b*seq+i with mask == 0; sel_count[b] per sequence; sel_off[b] = number
+ * of refreshed tokens in sequences before b, sel_off[batch] = total.
+ * sel_idx [batch*seq], sel_count [batch], sel_off [batch+1], all int32; any of
+ * the three may be NULL.
+ */
+dare_status dare_k_compact(const uint8_t* mask, int batch, int seq,
+                           int32_t* sel_idx, int32_t* sel_count,
+                           int32_t* sel_off, void* hip_stream);
+
+/*
+ * Bidirectional multi-head attention for selected query rows (App. E.2; Alg. 1
+ * line 10; Alg. 2 line 8):
+ *   out[t, h] = softmax(q[t, h] . K_b[:, h]^T / sqrt(head_dim)) V_b[:, h]
+ * for every head h and every token t of the row set; b = t / seq is the
+ * sequence of t, and keys/values are all seq rows of that sequence.
+ * Row set: all tokens when idx == NULL; else idx[sel_off[b] .. sel_off[b+1]) for
+ * each sequence b (idx, sel_off as produced by dare_k_compact).
+ *   q, k, v, out  [batch*seq, n_heads*head_dim] dtype, token-indexed rows
+ *   work          scratch of work_bytes bytes (may be NULL/0: then the key range
+ *                 is never split across workgroups)
+ */
+dare_status dare_k_attention(int dtype, const void* q, const void* k,
+                             const void* v, void* out, int batch, int seq,
+                             int n_heads, int head_dim, const int32_t* idx,
+                             const int32_t* sel_off, void* work,
+                             uint64_t work_bytes, void* hip_stream);
+
+/*
+ * Row copy between token-indexed buffers: dst[t] = src[t] for t in idx[0..*m_dev)
+ * (idx != NULL) or for all n_rows rows (idx == NULL).  row_bytes is a multiple
+ * of 16.  Used to mirror the layer output between out and o_cache when they are
+ * different buffers (Alg. 2 lines 9-10).
+ */
+dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows,
+                             int row_bytes, const int32_t* idx,
+                             const int32_t* m_dev, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DARE_KERNELS_H */

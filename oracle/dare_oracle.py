@@ -40,6 +40,19 @@ Readings taken where the paper is silent or has two forms:
   * a dense or DARE-O step writes the dense K, V into the K/V caches, so a later
     DARE-KV step starts from valid rows
   * index lists are ascending flat token ids b*T + i.
+  * precision.  The paper runs in BF16 (Sec. 5, App. A): the tensors its
+    algorithms name -- Q, K, V, the attention rows before Wo, the layer output --
+    are bf16 tensors, with wide accumulation inside each product.  ``storage=None``
+    (default) keeps everything in float64: that is the mathematical definition and
+    what the fp32 path is checked against.  ``storage="bf16"`` rounds Q, K, V and
+    the attention rows to bf16 (one rounding from float64, ties to even) at the
+    point the algorithm produces them; all arithmetic stays float64.  The drift
+    score is always taken from the unrounded query.  In that mode the returned
+    "out", "k_cache", "v_cache" are what the next step reads (rounded), and
+    "exact" holds the same tensors before their final rounding, which is what a
+    bf16 result is compared with (it may differ by half a bf16 ulp plus the
+    propagated error; comparing rounded with rounded would turn a harmless
+    last-bit flip into a whole ulp).
 
 Parity pinning: every function here is pinned by tests/test_oracle_pins.py
 (brute force in Python loops, closed forms, invariants).  The paper prints no
@@ -59,6 +72,22 @@ _DENOM_FLOOR = 1e-30
 
 def _f64(a):
     return np.asarray(a, dtype=np.float64)
+
+
+def round_storage(a, storage):
+    """Round float64 values to the storage format: None = keep, "bf16" = nearest
+    bfloat16 (8 significant bits, ties to even), in one rounding."""
+    a = _f64(a)
+    if storage is None:
+        return a
+    if storage != "bf16":
+        raise ValueError("storage must be None or 'bf16'")
+    u = np.ascontiguousarray(a).view(np.uint64)
+    drop = np.uint64(45)                      # 52 - 7 explicit significand bits
+    half = (np.uint64(1) << np.uint64(44)) - np.uint64(1)
+    odd = (u >> drop) & np.uint64(1)
+    r = ((u + half + odd) >> drop) << drop
+    return r.view(np.float64).reshape(a.shape)
 
 
 def drift_scores(q, p):
@@ -126,14 +155,15 @@ def dense_layer(x, wq, wk, wv, wo, n_heads):
 
 
 def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
-               n_heads, score_head=0):
+               n_heads, score_head=0, storage=None):
     """One step of the layer in mode DENSE / KV (Alg. 1) / O (Alg. 2) / KVO.
 
     x [B,T,d]; w* [d,d]; q_prev [B,T,Dh] (or [B,T,d] when score_head = -1);
     k_cache, v_cache, o_cache [B,T,d] hold the previous step's state.
     Returns a dict with out, k_cache, v_cache, o_cache, q_prev (all updated,
     float64), scores [B,T] float64, reuse_mask uint8 [B,T] (1 = reused),
-    sel_idx, sel_count, sel_off.
+    sel_idx, sel_count, sel_off, and exact = {out, k_cache, v_cache} before the
+    final storage rounding (identical to the former when storage is None).
     """
     if mode not in (MODE_DENSE, MODE_KV, MODE_O, MODE_KVO):
         raise ValueError("unknown mode")
@@ -155,39 +185,46 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
     else:
         reuse = reuse_decision(scores, tau)
     sel_idx, sel_count, sel_off = selection(reuse)
+    Qs = round_storage(Q, storage)
 
     # Keys and values.
     if mode in (MODE_KV, MODE_KVO):
         # Alg. 1 lines 6-9: refresh the selected rows, keep the cached ones.
-        K = _f64(k_cache).copy()
-        V = _f64(v_cache).copy()
+        K_exact = _f64(k_cache).copy()
+        V_exact = _f64(v_cache).copy()
         for b in range(B):
             rows = np.flatnonzero(~reuse[b])
-            K[b, rows] = x[b, rows] @ wk
-            V[b, rows] = x[b, rows] @ wv
+            K_exact[b, rows] = x[b, rows] @ wk
+            V_exact[b, rows] = x[b, rows] @ wv
     else:
         # Alg. 2 line 7 / App. E.2.
-        K = x @ wk
-        V = x @ wv
+        K_exact = x @ wk
+        V_exact = x @ wv
+    K = round_storage(K_exact, storage)
+    V = round_storage(V_exact, storage)
 
     # Attention and output projection.
     if mode in (MODE_O, MODE_KVO):
         # Alg. 2 lines 6, 8-11 with the cache holding rows after Wo.
-        out = _f64(o_cache).copy()
+        out_exact = _f64(o_cache).copy()
         for b in range(B):
             rows = np.flatnonzero(~reuse[b])
-            out[b, rows] = attention_rows(Q[b, rows], K[b], V[b], n_heads) @ wo
+            attn = round_storage(attention_rows(Qs[b, rows], K[b], V[b], n_heads), storage)
+            out_exact[b, rows] = attn @ wo
     else:
         # Alg. 1 lines 10-11.
-        out = np.empty((B, T, d), dtype=np.float64)
+        out_exact = np.empty((B, T, d), dtype=np.float64)
         for b in range(B):
-            out[b] = attention_rows(Q[b], K[b], V[b], n_heads) @ wo
+            attn = round_storage(attention_rows(Qs[b], K[b], V[b], n_heads), storage)
+            out_exact[b] = attn @ wo
+    out = round_storage(out_exact, storage)
 
     return {
         "out": out,
         "k_cache": K,
         "v_cache": V,
         "o_cache": out.copy(),
+        "exact": {"out": out_exact, "k_cache": K_exact, "v_cache": V_exact},
         "q_prev": q_sc.copy(),
         "scores": scores,
         "reuse_mask": reuse.astype(np.uint8),

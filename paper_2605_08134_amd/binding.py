@@ -1,0 +1,218 @@
+"""ctypes binding of libdare.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch provides device memory and streams);
+every computation happens in the library's HIP kernels.  There is no fallback:
+if libdare.so is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libdare.so")
+
+DARE_OK, DARE_ERR_INVALID_ARG, DARE_ERR_UNSUPPORTED, DARE_ERR_OOM, DARE_ERR_HIP = range(5)
+DARE_F32, DARE_BF16 = 0, 1
+MODE_DENSE, MODE_KV, MODE_O, MODE_KVO = 0, 1, 2, 3
+MODE_NAMES = {MODE_DENSE: "dense", MODE_KV: "kv", MODE_O: "o", MODE_KVO: "kvo"}
+
+EXPORTS = (
+    "dare_create", "dare_layer_step", "dare_destroy", "dare_last_error", "dare_version",
+    "dare_k_pack_weight", "dare_k_gemm", "dare_k_score", "dare_k_compact",
+    "dare_k_attention", "dare_k_copy_rows",
+)
+
+
+class DareConfig(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("hidden", ctypes.c_int32),
+        ("n_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("max_batch", ctypes.c_int32),
+        ("max_seq", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("score_head", ctypes.c_int32),
+        ("device", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
+    ]
+
+
+class DareError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("libdare status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library (loaded on first use; raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libdare.so is not built: run `python -m paper_2605_08134_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_uint64
+    L.dare_create.argtypes = [ctypes.POINTER(DareConfig), vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
+    L.dare_create.restype = i32
+    L.dare_layer_step.argtypes = [vp, i32, f32, i32, i32] + [vp] * 11
+    L.dare_layer_step.restype = i32
+    L.dare_destroy.argtypes = [vp]
+    L.dare_destroy.restype = i32
+    L.dare_last_error.argtypes = [vp]
+    L.dare_last_error.restype = ctypes.c_char_p
+    L.dare_version.argtypes = []
+    L.dare_version.restype = ctypes.c_char_p
+    L.dare_k_pack_weight.argtypes = [i32, vp, i32, i32, vp, i32, vp]
+    L.dare_k_pack_weight.restype = i32
+    L.dare_k_gemm.argtypes = [i32, vp, i32, vp, i32, i32, i32, vp, vp, ctypes.POINTER(vp), i32, i32,
+                              vp, i32, vp]
+    L.dare_k_gemm.restype = i32
+    L.dare_k_score.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp]
+    L.dare_k_score.restype = i32
+    L.dare_k_compact.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    L.dare_k_compact.restype = i32
+    L.dare_k_attention.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, u64, vp]
+    L.dare_k_attention.restype = i32
+    L.dare_k_copy_rows.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    L.dare_k_copy_rows.restype = i32
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "tensor must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _torch_dtype(dtype):
+    import torch
+    return torch.bfloat16 if dtype == DARE_BF16 else torch.float32
+
+
+def _check(st, ctx=None):
+    if st != DARE_OK:
+        msg = lib().dare_last_error(ctx)
+        raise DareError(st, msg.decode() if msg else "")
+
+
+def dare_version():
+    return lib().dare_version().decode()
+
+
+class DareLayer:
+    """dare_create / dare_layer_step / dare_destroy for one layer's weights."""
+
+    def __init__(self, wq, wk, wv, wo, n_heads, max_batch, max_seq, score_head=0, stream=None):
+        import torch
+        d = wq.shape[0]
+        dtype = DARE_BF16 if wq.dtype == torch.bfloat16 else DARE_F32
+        for w in (wq, wk, wv, wo):
+            assert w.is_cuda and w.shape == (d, d) and w.dtype == wq.dtype
+        self.cfg = DareConfig(ctypes.sizeof(DareConfig), d, n_heads, d // n_heads, max_batch, max_seq,
+                              dtype, score_head, wq.device.index or 0, 0)
+        self.dtype = dtype
+        self.hidden, self.n_heads, self.head_dim = d, n_heads, d // n_heads
+        self.score_width = d if score_head < 0 else self.head_dim
+        self.device = wq.device
+        self._ctx = ctypes.c_void_p()
+        st = lib().dare_create(ctypes.byref(self.cfg), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+                               _stream(stream), ctypes.byref(self._ctx))
+        _check(st, None)
+
+    def new_state(self, batch, seq):
+        """Zeroed caches for dare_layer_step (a DENSE step fills them)."""
+        import torch
+        td = _torch_dtype(self.dtype)
+        z = lambda *s, dt=td: torch.zeros(*s, dtype=dt, device=self.device)
+        return {
+            "q_prev": z(batch, seq, self.score_width, dt=torch.float32),
+            "k_cache": z(batch, seq, self.hidden),
+            "v_cache": z(batch, seq, self.hidden),
+            "o_cache": z(batch, seq, self.hidden),
+        }
+
+    def layer_step(self, mode, threshold, hidden, q_prev, k_cache, v_cache, o_cache, out,
+                   reuse_mask, sel_idx=None, sel_count=None, scores=None, stream=None):
+        batch, seq, _ = hidden.shape
+        st = lib().dare_layer_step(self._ctx, mode, threshold, batch, seq, _ptr(hidden), _ptr(q_prev),
+                                   _ptr(k_cache), _ptr(v_cache), _ptr(o_cache), _ptr(out),
+                                   _ptr(reuse_mask), _ptr(sel_idx), _ptr(sel_count), _ptr(scores),
+                                   _stream(stream))
+        _check(st, self._ctx)
+
+    def destroy(self):
+        if self._ctx:
+            lib().dare_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+# ---- kernel-level entry points ---------------------------------------------------------
+
+def dare_k_pack_weight(w, stream=None):
+    import torch
+    k, n = w.shape
+    wt = torch.empty((n, k), dtype=w.dtype, device=w.device)
+    dtype = DARE_BF16 if w.dtype == torch.bfloat16 else DARE_F32
+    _check(lib().dare_k_pack_weight(dtype, _ptr(w), k, n, _ptr(wt), k, _stream(stream)))
+    return wt
+
+
+def dare_k_gemm(a, wt, outs, seg_n, idx=None, m_dev=None, m_max=None, c32=None, stream=None):
+    import torch
+    n, k = wt.shape
+    dtype = DARE_BF16 if a.dtype == torch.bfloat16 else DARE_F32
+    arr = (ctypes.c_void_p * 3)(*[_ptr(o) for o in list(outs) + [None] * (3 - len(outs))])
+    ldc = next(o for o in outs if o is not None).shape[-1] if any(o is not None for o in outs) else seg_n
+    if m_max is None:
+        m_max = a.shape[0] if idx is None else idx.shape[0]
+    _check(lib().dare_k_gemm(dtype, _ptr(a), a.shape[-1], _ptr(wt), n, k, m_max, _ptr(idx), _ptr(m_dev),
+                             arr, ldc, seg_n, _ptr(c32), 0 if c32 is None else c32.shape[-1],
+                             _stream(stream)))
+
+
+def dare_k_score(q_new, q_prev, threshold, force_refresh, scores, mask, stream=None):
+    n_tokens, width = q_prev.shape[0], q_prev.shape[-1]
+    _check(lib().dare_k_score(_ptr(q_new), q_new.shape[-1], width, _ptr(q_prev), n_tokens, threshold,
+                              int(force_refresh), _ptr(scores), _ptr(mask), _stream(stream)))
+
+
+def dare_k_compact(mask, batch, seq, sel_idx, sel_count, sel_off, stream=None):
+    _check(lib().dare_k_compact(_ptr(mask), batch, seq, _ptr(sel_idx), _ptr(sel_count), _ptr(sel_off),
+                                _stream(stream)))
+
+
+def dare_k_attention(q, k, v, out, batch, seq, n_heads, head_dim, idx=None, sel_off=None, work=None,
+                     stream=None):
+    import torch
+    dtype = DARE_BF16 if q.dtype == torch.bfloat16 else DARE_F32
+    wb = 0 if work is None else work.numel() * work.element_size()
+    _check(lib().dare_k_attention(dtype, _ptr(q), _ptr(k), _ptr(v), _ptr(out), batch, seq, n_heads,
+                                  head_dim, _ptr(idx), _ptr(sel_off), _ptr(work), wb, _stream(stream)))
+
+
+def dare_k_copy_rows(src, dst, idx=None, m_dev=None, stream=None):
+    n_rows = src.shape[0]
+    row_bytes = src.shape[-1] * src.element_size()
+    _check(lib().dare_k_copy_rows(_ptr(src), _ptr(dst), n_rows, row_bytes, _ptr(idx), _ptr(m_dev),
+                                  _stream(stream)))

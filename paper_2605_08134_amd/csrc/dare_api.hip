@@ -1,0 +1,393 @@
+// C ABI of libdare: context, argument checks and the sequence of kernel launches
+// that makes one layer step (Alg. 1, Alg. 2, App. E.2 of the paper).  Host code
+// only; every stage runs in the kernels of the other .hip files.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "dare_common.h"
+
+using namespace dare;
+
+struct dare_ctx {
+  dare_config cfg;
+  size_t esize;        // bytes per element of cfg.dtype
+  int score_width;     // head_dim, or hidden when the whole query is scored
+  void* wqkv_t;        // [3d, d] packed Wq | Wk | Wv
+  void* wo_t;          // [d, d] packed Wo
+  void* q_buf;         // [max tokens, d] queries, token-indexed
+  void* attn_buf;      // [max tokens, d] attention rows before Wo, token-indexed
+  float* q_new;        // [max tokens, score_width] fp32 scored query of this step
+  int32_t* sel_idx;    // [max tokens]
+  int32_t* sel_off;    // [max_batch + 1]
+  void* attn_work;
+  uint64_t attn_work_bytes;
+  std::string err;
+};
+
+namespace {
+
+thread_local std::string g_create_err;
+
+dare_status fail(dare_ctx* ctx, dare_status st, const char* what) {
+  if (ctx) ctx->err = what; else g_create_err = what;
+  return st;
+}
+
+dare_status fail_hip(dare_ctx* ctx, hipError_t e, const char* where) {
+  std::string m = std::string(where) + ": " + hipGetErrorString(e);
+  if (ctx) ctx->err = m; else g_create_err = m;
+  return e == hipErrorOutOfMemory ? DARE_ERR_OOM : DARE_ERR_HIP;
+}
+
+struct DeviceGuard {
+  int prev = -1;
+  bool changed = false;
+  hipError_t enter(int dev) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e != hipSuccess) return e;
+    if (prev != dev) {
+      e = hipSetDevice(dev);
+      changed = e == hipSuccess;
+    }
+    return e;
+  }
+  ~DeviceGuard() {
+    if (changed) (void)hipSetDevice(prev);
+  }
+};
+
+void free_ctx(dare_ctx* c) {
+  if (!c) return;
+  void* bufs[] = {c->wqkv_t, c->wo_t, c->q_buf, c->attn_buf, c->q_new, c->sel_idx, c->sel_off,
+                  c->attn_work};
+  for (void* b : bufs)
+    if (b) (void)hipFree(b);
+  delete c;
+}
+
+hipError_t gemm(const dare_ctx* c, const GemmArgs& g, hipStream_t s) {
+  return c->cfg.dtype == DARE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+}
+hipError_t attn(const dare_ctx* c, const AttnArgs& a, hipStream_t s) {
+  return c->cfg.dtype == DARE_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dare_version(void) { return "0.1"; }
+
+const char* dare_last_error(const dare_ctx* ctx) {
+  return ctx ? ctx->err.c_str() : g_create_err.c_str();
+}
+
+dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, const void* wv,
+                        const void* wo, void* hip_stream, dare_ctx** out_ctx) {
+  if (out_ctx) *out_ctx = nullptr;
+  if (!cfg || !out_ctx) return fail(nullptr, DARE_ERR_INVALID_ARG, "null config or out_ctx");
+  if (cfg->struct_size != sizeof(dare_config))
+    return fail(nullptr, DARE_ERR_INVALID_ARG, "struct_size does not match this library");
+  if (!wq || !wk || !wv || !wo) return fail(nullptr, DARE_ERR_INVALID_ARG, "null weight pointer");
+  if (cfg->flags != 0) return fail(nullptr, DARE_ERR_INVALID_ARG, "flags must be 0");
+  if (cfg->dtype != DARE_F32 && cfg->dtype != DARE_BF16)
+    return fail(nullptr, DARE_ERR_INVALID_ARG, "unknown dtype");
+  if (cfg->hidden < 1 || cfg->n_heads < 1 || cfg->head_dim < 1 || cfg->max_batch < 1 ||
+      cfg->max_seq < 1 || cfg->device < 0)
+    return fail(nullptr, DARE_ERR_INVALID_ARG, "non-positive size");
+  if ((long)cfg->n_heads * cfg->head_dim != cfg->hidden)
+    return fail(nullptr, DARE_ERR_INVALID_ARG, "hidden != n_heads * head_dim");
+  if (cfg->score_head != 0 && cfg->score_head != -1)
+    return fail(nullptr, DARE_ERR_UNSUPPORTED, "score_head must be 0 or -1");
+  if (cfg->head_dim != 64 && cfg->head_dim != 128)
+    return fail(nullptr, DARE_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+  if (cfg->hidden % 64 != 0) return fail(nullptr, DARE_ERR_UNSUPPORTED, "hidden must be a multiple of 64");
+  const long max_tok = (long)cfg->max_batch * cfg->max_seq;
+  if (max_tok > (1l << 30) / 2) return fail(nullptr, DARE_ERR_UNSUPPORTED, "max_batch * max_seq too large");
+
+  DeviceGuard guard;
+  hipError_t e = guard.enter(cfg->device);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "hipSetDevice");
+
+  dare_ctx* c = new (std::nothrow) dare_ctx();
+  if (!c) return fail(nullptr, DARE_ERR_OOM, "host allocation failed");
+  c->cfg = *cfg;
+  c->esize = cfg->dtype == DARE_BF16 ? 2 : 4;
+  c->score_width = cfg->score_head < 0 ? cfg->hidden : cfg->head_dim;
+  c->wqkv_t = c->wo_t = c->q_buf = c->attn_buf = c->attn_work = nullptr;
+  c->q_new = nullptr;
+  c->sel_idx = c->sel_off = nullptr;
+  const size_t d = cfg->hidden;
+  c->attn_work_bytes = cfg->dtype == DARE_BF16
+                           ? attn_bf16_work_bytes(cfg->max_batch, cfg->max_seq, cfg->n_heads, cfg->head_dim)
+                           : 0;
+  struct { void** p; size_t bytes; } allocs[] = {
+      {&c->wqkv_t, 3 * d * d * c->esize},
+      {&c->wo_t, d * d * c->esize},
+      {&c->q_buf, (size_t)max_tok * d * c->esize},
+      {&c->attn_buf, (size_t)max_tok * d * c->esize},
+      {(void**)&c->q_new, (size_t)max_tok * c->score_width * sizeof(float)},
+      {(void**)&c->sel_idx, (size_t)max_tok * sizeof(int32_t)},
+      {(void**)&c->sel_off, ((size_t)cfg->max_batch + 1) * sizeof(int32_t)},
+      {&c->attn_work, (size_t)c->attn_work_bytes},
+  };
+  for (auto& a : allocs) {
+    if (a.bytes == 0) continue;
+    e = hipMalloc(a.p, a.bytes);
+    if (e != hipSuccess) {
+      *a.p = nullptr;
+      dare_status st = fail_hip(nullptr, e, "hipMalloc");
+      free_ctx(c);
+      return st;
+    }
+  }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const void* w3[3] = {wq, wk, wv};
+  for (int i = 0; i < 3 && e == hipSuccess; ++i)
+    e = launch_pack_weight(cfg->dtype, w3[i], cfg->hidden, cfg->hidden,
+                           static_cast<char*>(c->wqkv_t) + (size_t)i * d * d * c->esize, cfg->hidden, s);
+  if (e == hipSuccess) e = launch_pack_weight(cfg->dtype, wo, cfg->hidden, cfg->hidden, c->wo_t, cfg->hidden, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) {
+    dare_status st = fail_hip(nullptr, e, "weight packing");
+    free_ctx(c);
+    return st;
+  }
+  *out_ctx = c;
+  return DARE_OK;
+}
+
+dare_status dare_destroy(dare_ctx* ctx) {
+  if (!ctx) return DARE_OK;
+  DeviceGuard guard;
+  (void)guard.enter(ctx->cfg.device);
+  free_ctx(ctx);
+  return DARE_OK;
+}
+
+dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch, int seq,
+                            const void* hidden, float* q_prev, void* k_cache, void* v_cache,
+                            void* o_cache, void* out, uint8_t* reuse_mask, int32_t* sel_idx,
+                            int32_t* sel_count, float* scores, void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (mode != DARE_MODE_DENSE && mode != DARE_MODE_KV && mode != DARE_MODE_O && mode != DARE_MODE_KVO)
+    return fail(ctx, DARE_ERR_INVALID_ARG, "unknown mode");
+  if (!hidden || !q_prev || !k_cache || !v_cache || !o_cache || !out || !reuse_mask)
+    return fail(ctx, DARE_ERR_INVALID_ARG, "null required pointer");
+  if (batch < 1 || seq < 1) return fail(ctx, DARE_ERR_INVALID_ARG, "batch and seq must be >= 1");
+  if (batch > ctx->cfg.max_batch || seq > ctx->cfg.max_seq)
+    return fail(ctx, DARE_ERR_INVALID_ARG, "batch or seq exceeds the context's maximum");
+  if (std::isnan(threshold)) return fail(ctx, DARE_ERR_INVALID_ARG, "threshold is NaN");
+
+  const dare_config& cf = ctx->cfg;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int d = cf.hidden, n_tok = batch * seq, sw = ctx->score_width;
+  const size_t es = ctx->esize;
+  const char* wq_t = static_cast<const char*>(ctx->wqkv_t);
+  const char* wkv_t = wq_t + (size_t)d * d * es;
+  const bool sel_kv = mode == DARE_MODE_KV || mode == DARE_MODE_KVO;
+  const bool sel_o = mode == DARE_MODE_O || mode == DARE_MODE_KVO;
+  const int32_t* n_sel = ctx->sel_off + batch;  // device count of refreshed tokens
+  hipError_t e;
+
+  // 1. Query projection feeding the score (Alg. 1/2 line 2), together with whatever
+  //    else this mode projects for all rows.
+  GemmArgs g{};
+  g.a = hidden;
+  g.lda = d;
+  g.k = d;
+  g.m_max = n_tok;
+  g.ldc = d;
+  g.seg_n = d;
+  g.c32 = ctx->q_new;
+  g.c32_cols = sw;
+  g.wt = wq_t;
+  if (mode == DARE_MODE_DENSE || mode == DARE_MODE_O) {
+    g.n = 3 * d;  // Q, K, V for every row (App. E.2; Alg. 2 lines 2 and 7)
+    g.c[0] = ctx->q_buf;
+    g.c[1] = k_cache;
+    g.c[2] = v_cache;
+  } else if (mode == DARE_MODE_KV) {
+    g.n = d;  // Q for every row (Alg. 1 line 2)
+    g.c[0] = ctx->q_buf;
+  } else {
+    g.n = sw;  // only the scored columns of Q for every row
+  }
+  if ((e = gemm(ctx, g, s)) != hipSuccess) return fail_hip(ctx, e, "query projection");
+
+  // 2. Drift score, reuse decision, score-cache update (Alg. 1/2 lines 3-5).
+  e = launch_score(ctx->q_new, sw, sw, q_prev, n_tok, threshold, mode == DARE_MODE_DENSE, scores,
+                   nullptr, reuse_mask, s);
+  if (e != hipSuccess) return fail_hip(ctx, e, "score");
+
+  // 3. Index list of the refreshed tokens.
+  if (mode != DARE_MODE_DENSE || sel_idx || sel_count) {
+    e = launch_compact(reuse_mask, batch, seq, ctx->sel_idx, sel_idx, sel_count, nullptr,
+                       ctx->sel_off, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "compaction");
+  }
+
+  // 4. Projections of the refreshed rows (Alg. 1 lines 6-9), written straight into
+  //    the token-indexed caches / query buffer.
+  if (sel_kv) {
+    GemmArgs r{};
+    r.a = hidden;
+    r.lda = d;
+    r.k = d;
+    r.m_max = n_tok;
+    r.idx = ctx->sel_idx;
+    r.m_dev = n_sel;
+    r.ldc = d;
+    r.seg_n = d;
+    if (mode == DARE_MODE_KV) {
+      r.wt = wkv_t;
+      r.n = 2 * d;
+      r.c[0] = k_cache;
+      r.c[1] = v_cache;
+    } else {
+      r.wt = wq_t;
+      r.n = 3 * d;
+      r.c[0] = ctx->q_buf;
+      r.c[1] = k_cache;
+      r.c[2] = v_cache;
+    }
+    if ((e = gemm(ctx, r, s)) != hipSuccess) return fail_hip(ctx, e, "refreshed-row projection");
+  }
+
+  // 5. Attention (Alg. 1 line 10 / Alg. 2 line 8).
+  AttnArgs a{};
+  a.q = ctx->q_buf;
+  a.k = k_cache;
+  a.v = v_cache;
+  a.out = ctx->attn_buf;
+  a.batch = batch;
+  a.seq = seq;
+  a.n_heads = cf.n_heads;
+  a.head_dim = cf.head_dim;
+  a.idx = sel_o ? ctx->sel_idx : nullptr;
+  a.sel_off = sel_o ? ctx->sel_off : nullptr;
+  a.work = ctx->attn_work;
+  a.work_bytes = ctx->attn_work_bytes;
+  if ((e = attn(ctx, a, s)) != hipSuccess) return fail_hip(ctx, e, "attention");
+
+  // 6. Output projection (Alg. 1 line 11; Alg. 2 lines 9-11 with the cache after Wo).
+  GemmArgs o{};
+  o.a = ctx->attn_buf;
+  o.lda = d;
+  o.wt = ctx->wo_t;
+  o.n = d;
+  o.k = d;
+  o.m_max = n_tok;
+  o.ldc = d;
+  o.seg_n = d;
+  if (sel_o) {
+    o.idx = ctx->sel_idx;
+    o.m_dev = n_sel;
+    o.c[0] = o_cache;
+  } else {
+    o.c[0] = out;
+  }
+  if ((e = gemm(ctx, o, s)) != hipSuccess) return fail_hip(ctx, e, "output projection");
+
+  // 7. Keep out and o_cache equal when they are different buffers.
+  if (out != o_cache) {
+    e = sel_o ? launch_copy_rows(o_cache, out, n_tok, (int)(d * es), nullptr, nullptr, s)
+              : launch_copy_rows(out, o_cache, n_tok, (int)(d * es), nullptr, nullptr, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "output copy");
+  }
+  return DARE_OK;
+}
+
+// ---------------------------------------------------------------------------
+// kernel-level entry points
+// ---------------------------------------------------------------------------
+dare_status dare_k_pack_weight(int dtype, const void* w, int rows_k, int cols_n, void* wt, int ldwt,
+                               void* hip_stream) {
+  if (!w || !wt || rows_k < 1 || cols_n < 1 || ldwt < rows_k) return DARE_ERR_INVALID_ARG;
+  if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_pack_weight(dtype, w, rows_k, cols_n, wt, ldwt, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_gemm(int dtype, const void* a, int lda, const void* wt, int n, int k, int m_max,
+                        const int32_t* idx, const int32_t* m_dev, void* const* c, int ldc, int seg_n,
+                        float* c32, int c32_cols, void* hip_stream) {
+  if (!a || !wt || !c || n < 1 || k < 1 || m_max < 0 || lda < k) return DARE_ERR_INVALID_ARG;
+  if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
+  if (seg_n < 1 || n % seg_n != 0 || n / seg_n > 3) return DARE_ERR_INVALID_ARG;
+  if (c32 && (c32_cols < 1 || c32_cols > n || c32_cols % 4 != 0)) return DARE_ERR_INVALID_ARG;
+  if (k % 64 != 0 || n % (dtype == DARE_BF16 ? 64 : 16) != 0 || seg_n % 4 != 0) return DARE_ERR_UNSUPPORTED;
+  GemmArgs g{};
+  g.a = a;
+  g.lda = lda;
+  g.wt = wt;
+  g.n = n;
+  g.k = k;
+  g.m_max = m_max;
+  g.idx = idx;
+  g.m_dev = m_dev;
+  for (int i = 0; i < n / seg_n; ++i) g.c[i] = c[i];
+  g.ldc = ldc;
+  g.seg_n = seg_n;
+  g.c32 = c32;
+  g.c32_cols = c32 ? c32_cols : 0;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = dtype == DARE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_score(const float* q_new, int ld_new, int width, float* q_prev, int n_tokens,
+                         float threshold, int force_refresh, float* scores, uint8_t* mask,
+                         void* hip_stream) {
+  if (!q_new || !q_prev || !mask || width < 1 || ld_new < width || n_tokens < 0 || std::isnan(threshold))
+    return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_score(q_new, ld_new, width, q_prev, n_tokens, threshold, force_refresh, scores,
+                              nullptr, mask, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_idx, int32_t* sel_count,
+                           int32_t* sel_off, void* hip_stream) {
+  if (!mask || batch < 1 || seq < 1 || batch > 65535) return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_compact(mask, batch, seq, sel_idx, nullptr, sel_count, nullptr, sel_off,
+                                static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_attention(int dtype, const void* q, const void* k, const void* v, void* out, int batch,
+                             int seq, int n_heads, int head_dim, const int32_t* idx,
+                             const int32_t* sel_off, void* work, uint64_t work_bytes, void* hip_stream) {
+  if (!q || !k || !v || !out || batch < 1 || seq < 1 || n_heads < 1) return DARE_ERR_INVALID_ARG;
+  if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
+  if ((idx == nullptr) != (sel_off == nullptr)) return DARE_ERR_INVALID_ARG;
+  if (head_dim != 64 && head_dim != 128) return DARE_ERR_UNSUPPORTED;
+  if (batch > 65535 || n_heads > 65535) return DARE_ERR_UNSUPPORTED;
+  AttnArgs a{};
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.out = out;
+  a.batch = batch;
+  a.seq = seq;
+  a.n_heads = n_heads;
+  a.head_dim = head_dim;
+  a.idx = idx;
+  a.sel_off = sel_off;
+  a.work = work;
+  a.work_bytes = work_bytes;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = dtype == DARE_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows, int row_bytes, const int32_t* idx,
+                             const int32_t* m_dev, void* hip_stream) {
+  if (!src || !dst || n_rows < 0 || row_bytes < 16 || row_bytes % 16 != 0) return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_copy_rows(src, dst, n_rows, row_bytes, idx, m_dev, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+}  // extern "C"

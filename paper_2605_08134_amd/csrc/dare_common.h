@@ -1,0 +1,66 @@
+// Internal declarations shared by the HIP sources of libdare (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dare.h"
+#include "dare_kernels.h"
+
+namespace dare {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// ---- launchers (defined one per .hip file); all return a hipError_t ----------
+
+struct GemmArgs {
+  const void* a;      // [*, lda]
+  int lda;
+  const void* wt;     // [n, k] packed weight
+  int n, k;
+  int m_max;          // launch bound on the row count
+  const int32_t* idx; // optional row ids (gather of A rows = scatter of C rows)
+  const int32_t* m_dev; // optional device row count
+  void* c[3];         // output column segments
+  int ldc;
+  int seg_n;
+  float* c32;         // optional fp32 copy of columns [0, c32_cols)
+  int c32_cols;
+};
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
+
+struct AttnArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  int batch, seq, n_heads, head_dim;
+  const int32_t* idx;      // optional selected rows
+  const int32_t* sel_off;  // [batch+1] when idx != nullptr
+  void* work;
+  uint64_t work_bytes;
+};
+hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t s);
+uint64_t attn_bf16_work_bytes(int batch, int seq, int n_heads, int head_dim);
+
+hipError_t launch_pack_weight(int dtype, const void* w, int rows_k, int cols_n, void* wt,
+                              int ldwt, hipStream_t s);
+hipError_t launch_score(const float* q_new, int ld_new, int width, float* q_prev, int n_tokens,
+                        float threshold, int force_refresh, float* scores, float* scores2,
+                        uint8_t* mask, hipStream_t s);
+hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_idx,
+                          int32_t* sel_idx2, int32_t* sel_count, int32_t* sel_count2,
+                          int32_t* sel_off, hipStream_t s);
+hipError_t launch_copy_rows(const void* src, void* dst, int n_rows, int row_bytes,
+                            const int32_t* idx, const int32_t* m_dev, hipStream_t s);
+
+}  // namespace dare

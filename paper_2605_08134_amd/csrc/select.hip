@@ -1,0 +1,205 @@
+// The memory-bound stages of the layer step: weight re-packing, per-token drift
+// score + reuse decision + score-cache update, ordered compaction of the
+// refreshed set, and row copies between token-indexed buffers.
+#include "dare_common.h"
+
+namespace dare {
+namespace {
+
+// ---------------------------------------------------------------------------
+// wt[n, k] = w[k, n]: 32 x 32 tiles through LDS, both sides coalesced.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) pack_weight_kernel(const T* __restrict__ w, int rows_k,
+                                                         int cols_n, T* __restrict__ wt,
+                                                         int ldwt) {
+  __shared__ T tile[32][33];
+  const int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int r = ty; r < 32; r += 8) {
+    const int k = k0 + r, n = n0 + tx;
+    if (k < rows_k && n < cols_n) tile[r][tx] = w[(long)k * cols_n + n];
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int n = n0 + r, k = k0 + tx;
+    if (k < rows_k && n < cols_n) wt[(long)n * ldwt + k] = tile[tx][r];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Drift score (Sec. 3.1 eq. 1) and reuse decision (Sec. 3.2 eq. 2): one wave
+// per token.  The three sums use the same lane assignment and the same
+// butterfly, so a token whose query did not change gets dot == |q|^2 == |p|^2
+// bit for bit and a score of exactly 0.
+// ---------------------------------------------------------------------------
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__global__ void __launch_bounds__(256) score_kernel(const float* __restrict__ q_new, int ld_new,
+                                                   int width, float* __restrict__ q_prev,
+                                                   int n_tokens, float threshold,
+                                                   int force_refresh, float* __restrict__ scores,
+                                                   float* __restrict__ scores2,
+                                                   uint8_t* __restrict__ mask) {
+  const int lane = threadIdx.x & 63;
+  const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tok >= n_tokens) return;
+  const float* q = q_new + (long)tok * ld_new;
+  float* p = q_prev + (long)tok * width;
+  float dot = 0.f, nq = 0.f, np = 0.f;
+  for (int c = lane; c < width; c += 64) {
+    const float a = q[c], b = p[c];
+    dot = fmaf(a, b, dot);
+    nq = fmaf(a, a, nq);
+    np = fmaf(b, b, np);
+    p[c] = a;  // the score cache takes this step's query for every token
+  }
+  dot = wave_sum(dot);
+  nq = wave_sum(nq);
+  np = wave_sum(np);
+  if (lane == 0) {
+    const float den = fmaxf(sqrtf(nq * np), 1e-30f);
+    const float s = 1.0f - dot / den;
+    if (scores) scores[tok] = s;
+    if (scores2) scores2[tok] = s;
+    mask[tok] = (!force_refresh && s <= threshold) ? 1 : 0;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Ordered compaction (Alg. 1/2 line 5).  One workgroup per chunk of 1024
+// tokens of one sequence.  Its base offset is the number of refreshed tokens in
+// front of the chunk, counted from the mask bytes; inside the chunk a wave
+// ballot and a prefix over the wave counts give each refreshed token its slot.
+// No atomics: the list is ascending and identical from run to run.
+// ---------------------------------------------------------------------------
+constexpr int kChunk = 1024;
+
+__device__ inline int block_sum_256(int v, int* sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+__device__ inline int count_refreshed(const uint8_t* __restrict__ mask, long begin, long end) {
+  int c = 0;
+  for (long i = begin + threadIdx.x; i < end; i += 256) c += mask[i] == 0;
+  return c;
+}
+
+__global__ void __launch_bounds__(256) compact_kernel(const uint8_t* __restrict__ mask, int batch,
+                                                     int seq, int32_t* __restrict__ sel_idx,
+                                                     int32_t* __restrict__ sel_idx2,
+                                                     int32_t* __restrict__ sel_count,
+                                                     int32_t* __restrict__ sel_count2,
+                                                     int32_t* __restrict__ sel_off) {
+  __shared__ int sh[4];
+  __shared__ int wave_cnt[4];
+  const int b = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long seq_begin = (long)b * seq;
+  const long begin = seq_begin + (long)chunk * kChunk;
+  const long seq_end = seq_begin + seq;
+  const long end = begin + kChunk < seq_end ? begin + kChunk : seq_end;
+
+  int base = block_sum_256(count_refreshed(mask, 0, begin), sh);
+
+  if (chunk == 0) {
+    if (sel_off) sel_off[b] = base;
+    if (sel_count || sel_count2 || (sel_off && b == batch - 1)) {
+      const int cnt = block_sum_256(count_refreshed(mask, seq_begin, seq_end), sh);
+      if (threadIdx.x == 0) {
+        if (sel_count) sel_count[b] = cnt;
+        if (sel_count2) sel_count2[b] = cnt;
+        if (sel_off && b == batch - 1) sel_off[batch] = base + cnt;
+      }
+    }
+  }
+  if (!sel_idx && !sel_idx2) return;
+
+  for (long t0 = begin; t0 < end; t0 += 256) {
+    const long t = t0 + threadIdx.x;
+    const bool sel = t < end && mask[t] == 0;
+    const unsigned long long bal = __ballot(sel);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    __syncthreads();
+    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    __syncthreads();
+    int off = base;
+    for (int w = 0; w < wave; ++w) off += wave_cnt[w];
+    if (sel) {
+      if (sel_idx) sel_idx[off + before] = (int32_t)t;
+      if (sel_idx2) sel_idx2[off + before] = (int32_t)t;
+    }
+    base += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// dst[t] = src[t] for the listed (or all) rows: 16 bytes per lane, a row is a
+// contiguous run of full cache lines.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) copy_rows_kernel(const uint4* __restrict__ src,
+                                                       uint4* __restrict__ dst, int n_rows,
+                                                       int row_vec, const int32_t* __restrict__ idx,
+                                                       const int32_t* __restrict__ m_dev) {
+  const int m = idx ? (m_dev ? *m_dev : n_rows) : n_rows;
+  for (int r = blockIdx.x; r < m; r += gridDim.x) {
+    const long tok = idx ? (long)idx[r] : (long)r;
+    const uint4* s = src + tok * row_vec;
+    uint4* d = dst + tok * row_vec;
+    for (int c = threadIdx.x; c < row_vec; c += 256) d[c] = s[c];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_pack_weight(int dtype, const void* w, int rows_k, int cols_n, void* wt, int ldwt,
+                              hipStream_t s) {
+  dim3 grid((cols_n + 31) / 32, (rows_k + 31) / 32);
+  if (dtype == DARE_BF16)
+    hipLaunchKernelGGL(pack_weight_kernel<bf16_t>, grid, dim3(256), 0, s,
+                       static_cast<const bf16_t*>(w), rows_k, cols_n, static_cast<bf16_t*>(wt),
+                       ldwt);
+  else
+    hipLaunchKernelGGL(pack_weight_kernel<float>, grid, dim3(256), 0, s,
+                       static_cast<const float*>(w), rows_k, cols_n, static_cast<float*>(wt), ldwt);
+  return hipGetLastError();
+}
+
+hipError_t launch_score(const float* q_new, int ld_new, int width, float* q_prev, int n_tokens,
+                        float threshold, int force_refresh, float* scores, float* scores2,
+                        uint8_t* mask, hipStream_t s) {
+  if (n_tokens == 0) return hipSuccess;
+  hipLaunchKernelGGL(score_kernel, dim3((n_tokens + 3) / 4), dim3(256), 0, s, q_new, ld_new, width,
+                     q_prev, n_tokens, threshold, force_refresh, scores, scores2, mask);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_idx,
+                          int32_t* sel_idx2, int32_t* sel_count, int32_t* sel_count2,
+                          int32_t* sel_off, hipStream_t s) {
+  dim3 grid((seq + kChunk - 1) / kChunk, batch);
+  hipLaunchKernelGGL(compact_kernel, grid, dim3(256), 0, s, mask, batch, seq, sel_idx, sel_idx2,
+                     sel_count, sel_count2, sel_off);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_rows(const void* src, void* dst, int n_rows, int row_bytes,
+                            const int32_t* idx, const int32_t* m_dev, hipStream_t s) {
+  if (n_rows == 0) return hipSuccess;
+  const int grid = n_rows < 4096 ? n_rows : 4096;
+  hipLaunchKernelGGL(copy_rows_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint4*>(src),
+                     static_cast<uint4*>(dst), n_rows, row_bytes / 16, idx, m_dev);
+  return hipGetLastError();
+}
+
+}  // namespace dare

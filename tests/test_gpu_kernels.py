@@ -1,0 +1,212 @@
+"""GPU parity, stage by stage: each kernel-level entry point of the C ABI against
+the oracle's definition of that stage, on seeded inputs that span several tiles
+and a ragged tail."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dare_oracle as orc
+from paper_2605_08134_amd import synth
+from parity_util import assert_close, dev, host, rel_err, store
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_08134_amd import binding
+    binding.lib()
+    return binding
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_pack_weight_is_exact_transpose(B, dtype):
+    w = store(_rng(1).standard_normal((192, 320)), dtype)
+    wt = B.dare_k_pack_weight(dev(w, dtype))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(wt), w.T)
+
+
+@pytest.mark.parametrize("dtype,m,n,k,seg", [
+    ("bf16", 300, 384, 256, 128),     # 3 segments, ragged rows
+    ("bf16", 128, 128, 64, 128),      # exactly one tile, one k step
+    ("bf16", 1, 64, 128, 64),         # single row, narrow tile config
+    ("bf16", 517, 1024, 512, 1024),   # many tiles
+    ("f32", 150, 192, 64, 64),
+    ("f32", 64, 64, 64, 64),
+])
+def test_gemm_all_rows(B, dtype, m, n, k, seg):
+    r = _rng(m + n)
+    a = store(r.standard_normal((m, k)), dtype)
+    w = store(r.standard_normal((k, n)) * 0.05, dtype)
+    wt = B.dare_k_pack_weight(dev(w, dtype))
+    nseg = n // seg
+    outs = [torch.zeros((m, seg), dtype=wt.dtype, device="cuda") for _ in range(nseg)]
+    c32_cols = min(64, n)
+    c32 = torch.zeros((m, c32_cols), dtype=torch.float32, device="cuda")
+    B.dare_k_gemm(dev(a, dtype), wt, outs, seg, c32=c32)
+    torch.cuda.synchronize()
+    want = a.astype(np.float64) @ w.astype(np.float64)
+    got = np.concatenate([host(o) for o in outs], axis=1)
+    assert_close(got, want, dtype)
+    assert rel_err(host(c32), want[:, :c32_cols]) <= 2e-6     # fp32 accumulators, unrounded
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("count", [0, 1, 129, 205])
+def test_gemm_selected_rows_device_count(B, dtype, count):
+    r = _rng(count + 5)
+    n_tok, k, n = 400, 128, 256
+    a = store(r.standard_normal((n_tok, k)), dtype)
+    w = store(r.standard_normal((k, n)) * 0.05, dtype)
+    wt = B.dare_k_pack_weight(dev(w, dtype))
+    rows = np.sort(r.permutation(n_tok)[:count]).astype(np.int32)
+    idx = np.full(n_tok, 10 ** 6, dtype=np.int32)      # entries past the count must never be used
+    idx[:count] = rows
+    sentinel = store(np.full((n_tok, 128), 3.0), dtype)
+    outs = [dev(sentinel, dtype), dev(sentinel, dtype)]
+    m_dev = torch.tensor([count], dtype=torch.int32, device="cuda")
+    B.dare_k_gemm(dev(a, dtype), wt, outs, 128, idx=dev(idx), m_dev=m_dev, m_max=n_tok)
+    torch.cuda.synchronize()
+    got = np.concatenate([host(o) for o in outs], axis=1)
+    want = np.full((n_tok, n), 3.0)
+    want[rows] = a[rows].astype(np.float64) @ w.astype(np.float64)
+    untouched = np.setdiff1d(np.arange(n_tok), rows)
+    assert np.all(got[untouched] == 3.0)
+    if count:
+        assert_close(got[rows], want[rows], dtype)
+
+
+def test_score_kernel(B):
+    r = _rng(9)
+    n, w, ld = 333, 128, 160
+    q = r.standard_normal((n, ld)).astype(np.float32)
+    p = r.standard_normal((n, w)).astype(np.float32)
+    p[:40] = q[:40, :w]                      # unchanged tokens: score exactly 0
+    p[40:60] = 2.5 * q[40:60, :w]            # rescaled: score ~ 0
+    p[60:70] = -q[60:70, :w]                 # opposite: score 2
+    p[70] = 0.0                              # zero norm: cosine taken as 0
+    p[100:200] = q[100:200, :w] + 0.3 * r.standard_normal((100, w)).astype(np.float32)
+    want = orc.drift_scores(q[:, :w], p)
+    tau = 0.05
+    qd, pd = dev(q), dev(p)
+    scores = torch.zeros(n, dtype=torch.float32, device="cuda")
+    mask = torch.full((n,), 9, dtype=torch.uint8, device="cuda")
+    B.dare_k_score(qd, pd, tau, False, scores, mask)
+    torch.cuda.synchronize()
+    s = host(scores)
+    assert np.all(s[:40] == 0.0)
+    assert np.max(np.abs(s - want)) < 5e-7
+    assert s[70] == 1.0
+    ties = np.abs(want - np.float32(tau)) < 1e-6
+    assert np.array_equal(host(mask)[~ties], orc.reuse_decision(want, tau)[~ties].astype(np.uint8))
+    assert np.array_equal(host(pd), q[:, :w])                 # score cache replaced for every token
+    # force_refresh: scores still reported, mask all zero
+    B.dare_k_score(qd, dev(p), 2.5, True, scores, mask)
+    torch.cuda.synchronize()
+    assert not host(mask).any() and np.max(np.abs(host(scores) - want)) < 5e-7
+
+
+@pytest.mark.parametrize("batch,seq,frac", [(1, 128, 0.2), (3, 1000, 0.5), (2, 2500, 0.07),
+                                            (4, 64, 0.0), (2, 1024, 1.0), (8, 2048, 0.2)])
+def test_compaction_is_ordered_and_exact(B, batch, seq, frac):
+    r = _rng(batch * seq)
+    reuse = r.random((batch, seq)) >= frac
+    mask = dev(reuse.astype(np.uint8))
+    sel_idx = torch.full((batch * seq,), -1, dtype=torch.int32, device="cuda")
+    sel_count = torch.full((batch,), -1, dtype=torch.int32, device="cuda")
+    sel_off = torch.full((batch + 1,), -1, dtype=torch.int32, device="cuda")
+    B.dare_k_compact(mask, batch, seq, sel_idx, sel_count, sel_off)
+    torch.cuda.synchronize()
+    idx, cnt, off = orc.selection(reuse)
+    assert np.array_equal(host(sel_idx)[:len(idx)], idx)
+    assert np.all(host(sel_idx)[len(idx):] == -1)
+    assert np.array_equal(host(sel_count), cnt)
+    assert np.array_equal(host(sel_off), off)
+
+
+def _attn_case(seed, batch, seq, heads, dh, dtype, frac):
+    r = _rng(seed)
+    d = heads * dh
+    q = store(r.standard_normal((batch * seq, d)), dtype)
+    k = store(r.standard_normal((batch * seq, d)), dtype)
+    v = store(r.standard_normal((batch * seq, d)), dtype)
+    reuse = r.random((batch, seq)) >= frac
+    return q, k, v, reuse
+
+
+@pytest.mark.parametrize("dtype,batch,seq,heads,dh", [
+    ("bf16", 1, 256, 2, 128), ("bf16", 2, 200, 3, 128), ("bf16", 1, 1, 1, 128),
+    ("bf16", 2, 333, 2, 64), ("bf16", 1, 65, 1, 64),
+    ("f32", 1, 128, 4, 64), ("f32", 2, 77, 2, 128), ("f32", 1, 1100, 1, 64),
+])
+def test_attention_all_rows(B, dtype, batch, seq, heads, dh):
+    q, k, v, _ = _attn_case(seq + dh, batch, seq, heads, dh, dtype, 1.0)
+    out = torch.zeros((batch * seq, heads * dh), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32,
+                      device="cuda")
+    B.dare_k_attention(dev(q, dtype), dev(k, dtype), dev(v, dtype), out, batch, seq, heads, dh)
+    torch.cuda.synchronize()
+    got = host(out)
+    for b in range(batch):
+        sl = slice(b * seq, (b + 1) * seq)
+        want = orc.attention_rows(q[sl], k[sl], v[sl], heads)
+        assert_close(got[sl], want, dtype, slack=8.0)
+
+
+@pytest.mark.parametrize("dtype,batch,seq,heads,dh,frac", [
+    ("bf16", 2, 300, 2, 128, 0.2), ("bf16", 3, 200, 1, 128, 0.9), ("bf16", 2, 130, 2, 64, 0.5),
+    ("f32", 2, 100, 2, 64, 0.3),
+])
+def test_attention_selected_rows(B, dtype, batch, seq, heads, dh, frac):
+    q, k, v, reuse = _attn_case(seq + 3, batch, seq, heads, dh, dtype, frac)
+    reuse[0] = True if batch > 2 else reuse[0]          # a sequence with nothing selected
+    idx, cnt, off = orc.selection(reuse)
+    idx_full = np.full(batch * seq, 10 ** 6, dtype=np.int32)
+    idx_full[:len(idx)] = idx
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    out = torch.full((batch * seq, heads * dh), 5.0, dtype=tdt, device="cuda")
+    B.dare_k_attention(dev(q, dtype), dev(k, dtype), dev(v, dtype), out, batch, seq, heads, dh,
+                       idx=dev(idx_full), sel_off=dev(off))
+    torch.cuda.synchronize()
+    got = host(out)
+    for b in range(batch):
+        sl = slice(b * seq, (b + 1) * seq)
+        rows = np.flatnonzero(~reuse[b])
+        keep = np.flatnonzero(reuse[b])
+        assert np.all(got[sl][keep] == 5.0)               # unselected rows untouched
+        if len(rows):
+            want = orc.attention_rows(q[sl][rows], k[sl], v[sl], heads)
+            assert_close(got[sl][rows], want, dtype, slack=8.0)
+
+
+def test_attention_large_logits_are_stable(B):
+    q, k, v, _ = _attn_case(77, 1, 192, 1, 128, "bf16", 1.0)
+    q = store(q * 30.0, "bf16")
+    out = torch.zeros((192, 128), dtype=torch.bfloat16, device="cuda")
+    B.dare_k_attention(dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), out, 1, 192, 1, 128)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.all(np.isfinite(got))
+    assert rel_err(got, orc.attention_rows(q, k, v, 1)) <= 2e-2
+
+
+def test_copy_rows(B):
+    r = _rng(4)
+    src = r.standard_normal((100, 256)).astype(np.float32)
+    dst = torch.zeros((100, 256), dtype=torch.float32, device="cuda")
+    B.dare_k_copy_rows(dev(src), dst)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(dst), src)
+    dst.zero_()
+    rows = np.array([3, 4, 50, 99], dtype=np.int32)
+    idx = np.full(100, 10 ** 6, dtype=np.int32)
+    idx[:4] = rows
+    B.dare_k_copy_rows(dev(src), dst, idx=dev(idx), m_dev=torch.tensor([4], dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    want = np.zeros_like(src)
+    want[rows] = src[rows]
+    assert np.array_equal(host(dst), want)

@@ -1,0 +1,210 @@
+"""GPU parity of dare_layer_step against the oracle: every mode, the thresholds
+that reuse nothing / about half / everything, small ragged shapes, and the
+LLaDA-8B-shaped layer at full size."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dare_oracle as orc
+from paper_2605_08134_amd import synth
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+MODES = [orc.MODE_DENSE, orc.MODE_KV, orc.MODE_O, orc.MODE_KVO]
+
+
+def _run(case, gl, state, mode, tau, **kw):
+    want = pu.oracle_step(case, state, mode, tau)
+    got = gl.step(mode, tau, case["x_cur"], state, **kw)
+    return pu.check_step(got, want, state, mode, tau, case["dtype"]), got, want
+
+
+# ------------------------------------------------------------------ tiny fp32 layer
+@pytest.fixture(scope="module")
+def tiny():
+    case = synth.make_case("tiny", seed=1234)
+    state = pu.oracle_fill(case)
+    return case, state, pu.GpuLayer(case)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("which", ["zero", "median", "above_max", "nothing", "everything"])
+def test_tiny_fp32_all_modes_and_thresholds(tiny, mode, which):
+    case, state, gl = tiny
+    s = pu.oracle_step(case, state, orc.MODE_KV, 0.0)["scores"]
+    srt = np.sort(s.reshape(-1))
+    median = float(np.float32(0.5 * (srt[len(srt) // 2 - 1] + srt[len(srt) // 2])))
+    tau = {"zero": 0.0, "median": median, "above_max": float(s.max()) + 4e-6,
+           "nothing": -1.0, "everything": 2.5}[which]
+    if which == "median":
+        # the stable tokens' scores lie closer together than the tie band, so the
+        # median threshold has ties by construction: they are counted, not forbidden
+        want = pu.oracle_step(case, state, mode, tau)
+        got = gl.step(mode, tau, case["x_cur"], state)
+        info = pu.check_step(got, want, state, mode, tau, "f32", expect_no_ties=False)
+        print("median threshold: %d ties" % info["ties"])
+    else:
+        info, got, want = _run(case, gl, state, mode, tau)
+    n_reused = int(got["reuse_mask"].sum())
+    if mode == orc.MODE_DENSE or which in ("zero", "nothing"):
+        assert n_reused == 0          # every token of this input is perturbed: scores > 0
+    elif which in ("above_max", "everything"):
+        assert n_reused == case["seq"]
+    else:
+        assert 0.4 * case["seq"] <= n_reused <= 0.6 * case["seq"]
+
+
+def test_tiny_threshold_exactly_at_max_score_ties(tiny):
+    # tau equal to the largest score: that token is a tie by construction; the
+    # masks must agree everywhere else and the tie is counted.
+    case, state, gl = tiny
+    s = pu.oracle_step(case, state, orc.MODE_KV, 0.0)["scores"]
+    tau = float(np.float32(s.max()))
+    want = pu.oracle_step(case, state, orc.MODE_O, tau)
+    got = gl.step(orc.MODE_O, tau, case["x_cur"], state)
+    info = pu.check_step(got, want, state, orc.MODE_O, tau, "f32", expect_no_ties=False)
+    assert info["ties"] >= 1
+    assert int(got["reuse_mask"].sum()) >= case["seq"] - 1
+
+
+def test_tiny_separate_out_buffer_and_no_lists(tiny):
+    case, state, gl = tiny
+    tau = synth.TAU_SEPARATING
+    for mode in MODES:
+        want = pu.oracle_step(case, state, mode, tau)
+        got = gl.step(mode, tau, case["x_cur"], state, alias_out=False, want_lists=False)
+        pu.check_step(got, want, state, mode, tau, "f32")
+
+
+def test_tiny_two_steps_unchanged_input_scores_zero(tiny):
+    # second step on the same hidden states: every score is exactly 0 and tau = 0 reuses all
+    case, state, gl = tiny
+    first = gl.step(orc.MODE_KVO, -1.0, case["x_cur"], state)
+    st2 = {k: first[k] for k in ("q_prev", "k_cache", "v_cache", "o_cache")}
+    second = gl.step(orc.MODE_KVO, 0.0, case["x_cur"], st2)
+    assert np.all(second["scores"] == 0.0)
+    assert second["reuse_mask"].all()
+    assert np.array_equal(second["out"], first["out"])
+    assert np.array_equal(second["k_cache"], first["k_cache"])
+
+
+def test_tiny_is_deterministic(tiny):
+    case, state, gl = tiny
+    tau = synth.TAU_SEPARATING
+    a = gl.step(orc.MODE_KVO, tau, case["x_cur"], state)
+    b = gl.step(orc.MODE_KVO, tau, case["x_cur"], state)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_step_argument_errors_leave_buffers_untouched(tiny):
+    case, state, gl = tiny
+    B = gl.B
+    x = pu.dev(case["x_cur"], "f32")
+    st = {k: pu.dev(v) for k, v in state.items()}
+    before = {k: v.clone() for k, v in st.items()}
+    mask = torch.zeros((1, 128), dtype=torch.uint8, device="cuda")
+
+    def call(mode=1, tau=0.1, hidden=x, batch_hidden=None):
+        gl.layer.layer_step(mode, tau, hidden, st["q_prev"], st["k_cache"], st["v_cache"],
+                            st["o_cache"], st["o_cache"], mask)
+
+    for kw in (dict(mode=9), dict(tau=float("nan"))):
+        with pytest.raises(B.DareError) as ei:
+            call(**kw)
+        assert ei.value.status == B.DARE_ERR_INVALID_ARG
+    big = torch.zeros((2, 128, 256), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.DareError):
+        call(hidden=big)                      # batch 2 > max_batch 1
+    torch.cuda.synchronize()
+    for k in st:
+        assert torch.equal(st[k], before[k])
+
+
+# ------------------------------------------------------------------ small bf16 layers, ragged
+@pytest.mark.parametrize("shape", [
+    dict(batch=2, seq=320, hidden=512, n_heads=4, head_dim=128, fraction=0.2),
+    dict(batch=3, seq=100, hidden=256, n_heads=4, head_dim=64, fraction=(0.05, 0.5)),
+    dict(batch=1, seq=1, hidden=128, n_heads=1, head_dim=128, fraction=1.0),
+])
+@pytest.mark.parametrize("mode", MODES)
+def test_small_bf16(shape, mode):
+    case = synth.make_case("llada8b", seed=77, **shape)
+    state = pu.oracle_fill(case)
+    gl = pu.GpuLayer(case, max_batch=case["batch"] + 1, max_seq=case["seq"] + 37)
+    s = pu.oracle_step(case, state, orc.MODE_KV, 0.0)["scores"]
+    taus = [-1.0, 2.5] + ([pu.gap_threshold(s, 0.6)] if s.size > 4 else [])
+    for tau in taus:
+        _run(case, gl, state, mode, tau)
+    gl.layer.destroy()
+
+
+def test_small_fp32_head128_ragged():
+    case = synth.make_case("tiny", seed=5, batch=2, seq=75, hidden=256, n_heads=2, head_dim=128)
+    state = pu.oracle_fill(case)
+    gl = pu.GpuLayer(case)
+    for mode in MODES:
+        _run(case, gl, state, mode, synth.TAU_SEPARATING)
+
+
+# ------------------------------------------------------------------ LLaDA-8B-shaped layer, full size
+@pytest.fixture(scope="module")
+def llada():
+    case = synth.make_case("llada8b", seed=1234, fraction=0.20)
+    state = pu.oracle_fill(case)
+    return case, state, pu.GpuLayer(case)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_llada8b_layer_full_size(llada, mode):
+    case, state, gl = llada
+    tau = synth.TAU_SEPARATING
+    info, got, want = _run(case, gl, state, mode, tau)
+    if mode != orc.MODE_DENSE:
+        assert np.array_equal(got["reuse_mask"].astype(bool), ~case["perturbed"])
+        assert int(got["sel_count"][0]) == round(0.2 * case["seq"])
+    print("llada8b mode %d errors: %s" % (mode, info))
+
+
+def test_llada8b_against_unrounded_definition(llada):
+    # Information plus a loose bound: the bf16 path against the float64 oracle with NO
+    # storage rounding anywhere.  Rounding Q, K, V, the attention rows and the output
+    # to bf16 each moves the output by 1-2.4 % of its rms at the worst element (the
+    # output has 7-sigma elements), about 4 % together; 8e-2 bounds that with margin.
+    case, state, gl = llada
+    tau = synth.TAU_SEPARATING
+    for mode in (orc.MODE_DENSE, orc.MODE_KVO):
+        want = pu.oracle_step(case, state, mode, tau, storage=None)
+        got = gl.step(mode, tau, case["x_cur"], state)
+        err = pu.rel_err(got["out"], want["out"])
+        print("llada8b mode %d vs unrounded float64 definition: %.4f of rms" % (mode, err))
+        assert err <= 8e-2
+        assert np.array_equal(got["reuse_mask"], want["reuse_mask"])
+
+
+# ------------------------------------------------------------------ batch 8 x 2048, per-sequence fractions
+def test_llada8b_batch8_variable_rows():
+    case = synth.make_case("llada8b_b8", seed=4321)
+    tau = synth.TAU_SEPARATING
+    gl = pu.GpuLayer(case)
+    # sequences are independent: the oracle runs one sequence at a time
+    states = []
+    for b in range(case["batch"]):
+        one = dict(case, batch=1, x_prev=case["x_prev"][b:b + 1], x_cur=case["x_cur"][b:b + 1])
+        states.append((one, pu.oracle_fill(one)))
+    state = {k: np.concatenate([s[k] for _, s in states], axis=0) for k in states[0][1]}
+    got = gl.step(orc.MODE_KVO, tau, case["x_cur"], state)
+    assert np.array_equal(got["reuse_mask"].astype(bool), ~case["perturbed"])
+    assert np.array_equal(got["sel_count"], case["perturbed"].sum(axis=1))
+    assert len(set(got["sel_count"].tolist())) > 1
+    for b in (0, case["batch"] - 1):
+        one, st = states[b]
+        want = pu.oracle_step(one, st, orc.MODE_KVO, tau)
+        sub = {k: (v[b:b + 1] if v.ndim >= 2 and v.shape[0] == case["batch"] else v) for k, v in got.items()}
+        n_before = int(got["sel_count"][:b].sum())
+        n_b = int(got["sel_count"][b])
+        sub["sel_idx"] = np.concatenate([got["sel_idx"][n_before:n_before + n_b] - b * case["seq"],
+                                         np.full(case["seq"] - n_b, -1, dtype=np.int32)])
+        sub["sel_count"] = got["sel_count"][b:b + 1]
+        pu.check_step(sub, want, st, orc.MODE_KVO, tau, "bf16")

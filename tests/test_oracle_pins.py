@@ -424,3 +424,76 @@ def test_reused_tokens_obey_input_drift_bound():
     bound = 4 * d * tau * kappa ** 2 / (2 + tau * (kappa ** 2 - 1))
     diff2 = np.sum((x1 - x0) ** 2, axis=2)
     assert np.all(diff2[reuse] <= bound * (1 + 1e-9))
+
+
+# ----------------------------------------------------------------------------
+# bf16 storage model (the paper's runs are BF16: Sec. 5, App. A)
+# ----------------------------------------------------------------------------
+def test_round_storage_matches_bfloat16():
+    import torch
+    r = _rng(81)
+    a32 = (r.standard_normal(50000) * 10.0 ** r.integers(-5, 5, 50000)).astype(np.float32)
+    a32[:3] = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8)]     # ties go to even
+    want = torch.from_numpy(a32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(orc.round_storage(a32.astype(np.float64), "bf16"), want)
+    # one rounding from float64: 1 + 2^-8 + 2^-30 is above the tie and rounds up,
+    # whereas going through float32 first would land on the tie and round down
+    assert orc.round_storage(np.array([1.0 + 2.0 ** -8 + 2.0 ** -30]), "bf16")[0] == 1.0 + 2.0 ** -7
+    assert orc.round_storage(np.array([0.0, -0.0, 3.0, 256.0]), "bf16").tolist() == [0.0, -0.0, 3.0, 256.0]
+    x = r.standard_normal(10)
+    assert orc.round_storage(x, None) is not None and np.array_equal(orc.round_storage(x, None), x)
+    # idempotent
+    y = orc.round_storage(x, "bf16")
+    assert np.array_equal(orc.round_storage(y, "bf16"), y)
+    assert np.max(np.abs(y - x) / np.abs(x)) <= 2.0 ** -8
+
+
+def test_storage_model_rounds_exactly_the_named_tensors():
+    w, x0, x1, H = _case(83, B=2, T=9)
+    st = _fill(w, x0, H)
+    st = {k: (orc.round_storage(v, "bf16") if k != "q_prev" else v) for k, v in st.items()}
+    tau = _mid_tau(_step(orc.MODE_KVO, 0.0, w, x1, st, H)["scores"])
+    rb = lambda a: orc.round_storage(a, "bf16")
+    for mode in (orc.MODE_DENSE, orc.MODE_KV, orc.MODE_O, orc.MODE_KVO):
+        o = _step(mode, tau, w, x1, st, H, storage="bf16")
+        ref = _step(mode, tau, w, x1, st, H)
+        assert np.array_equal(o["scores"], ref["scores"])          # score from the unrounded query
+        assert np.array_equal(o["reuse_mask"], ref["reuse_mask"])
+        mask = o["reuse_mask"].astype(bool)
+        Q = rb(x1 @ w["wq"])
+        if mode in (orc.MODE_KV, orc.MODE_KVO):
+            Kx = np.where(mask[:, :, None], st["k_cache"], x1 @ w["wk"])
+            Vx = np.where(mask[:, :, None], st["v_cache"], x1 @ w["wv"])
+        else:
+            Kx, Vx = x1 @ w["wk"], x1 @ w["wv"]
+        assert np.allclose(o["exact"]["k_cache"], Kx, atol=1e-13)
+        assert np.array_equal(o["k_cache"], rb(o["exact"]["k_cache"]))
+        assert np.array_equal(o["v_cache"], rb(o["exact"]["v_cache"]))
+        assert np.array_equal(o["out"], rb(o["exact"]["out"]))
+        for b in range(2):
+            attn = rb(orc.attention_rows(Q[b], rb(Kx[b]), rb(Vx[b]), H))
+            want = attn @ w["wo"]
+            rows = ~mask[b] if mode in (orc.MODE_O, orc.MODE_KVO) else np.ones(9, bool)
+            assert np.allclose(o["exact"]["out"][b][rows], want[rows], rtol=1e-11, atol=1e-12)
+            if mode in (orc.MODE_O, orc.MODE_KVO):
+                assert np.array_equal(o["out"][b][~rows], st["o_cache"][b][~rows])
+        # the rounded model stays close to the unrounded definition
+        rms = np.sqrt(np.mean(ref["out"] ** 2))
+        assert np.max(np.abs(o["out"] - ref["out"])) / rms < 6e-2
+        assert np.max(np.abs(o["out"] - ref["out"])) > 0
+
+
+def test_storage_model_is_exact_on_representable_data():
+    # small integers: every intermediate that gets rounded is already a bf16 value
+    # when attention is uniform (Wq = 0), so both models agree bit for bit
+    r = _rng(85)
+    d, T, H = 4, 4, 1
+    wk = r.integers(-2, 3, (d, d)).astype(float)
+    wv = r.integers(-2, 3, (d, d)).astype(float)
+    wo = np.eye(d)
+    x = r.integers(-2, 3, (1, T, d)).astype(float) * 4.0      # sums of 4 values stay multiples of 1
+    z = np.zeros((1, T, d))
+    st = dict(q_prev=np.ones((1, T, d)), k_cache=z, v_cache=z, o_cache=z)
+    a = orc.layer_step(orc.MODE_DENSE, 0.0, x, np.zeros((d, d)), wk, wv, wo, **st, n_heads=H)
+    b = orc.layer_step(orc.MODE_DENSE, 0.0, x, np.zeros((d, d)), wk, wv, wo, **st, n_heads=H, storage="bf16")
+    assert np.array_equal(a["out"], b["out"]) and np.array_equal(a["k_cache"], b["k_cache"])

@@ -46,3 +46,16 @@ def test_per_sequence_fractions():
     assert n.min() >= 10 and n.max() <= 60 and len(set(n.tolist())) > 3
     x = h["x_cur"]
     assert np.array_equal(synth.round_to_bf16(x), x)
+
+
+def test_half_ulp_helper_of_the_parity_rule():
+    import sys, os
+    sys.path.insert(0, os.path.dirname(__file__))
+    import parity_util as pu
+    x = np.array([1.0, 1.99, 2.0, 0.75, -3.0, 1e-3])
+    spacing = np.array([2.0 ** -7, 2.0 ** -7, 2.0 ** -6, 2.0 ** -8, 2.0 ** -6, 2.0 ** -17])
+    assert np.array_equal(pu.half_ulp_bf16(x), spacing / 2)
+    r = np.random.Generator(np.random.PCG64(2)).standard_normal(10000) * 3
+    # rounding a value to bf16 never moves it by more than the helper says
+    assert np.all(np.abs(synth.round_to_bf16(r.astype(np.float32)).astype(np.float64) - r.astype(np.float32)) <= pu.half_ulp_bf16(r.astype(np.float32)))
+    assert pu.excess_err(synth.round_to_bf16(r.astype(np.float32)), r.astype(np.float32)) == 0.0
