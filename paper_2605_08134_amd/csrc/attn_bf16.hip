@@ -76,46 +76,44 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnDev p) {
 
   // staging assignment
   const int v_dg = tid % DG, v_kg = tid / DG;  // V: 8 channels x 4 keys per thread
-  const bool v_active = v_kg < BKV / 4;
-  uint4 rk[K_CH], rv[4];
-  auto load_global = [&](int kv0) {
+  constexpr bool kAllStageV = 256 / DG == BKV / 4;  // every thread has a V unit
+  const bool v_active = kAllStageV || v_kg < BKV / 4;
+  u32x4 rk[K_CH], rv[4];
+  auto load_global = [&](int kv0) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < K_CH; ++i) {
       const int ch = tid + i * 256;
       int key = kv0 + ch / DG;
       key = key < T ? key : T - 1;
-      rk[i] = *reinterpret_cast<const uint4*>(kbase + (long)key * p.d + (ch % DG) * 8);
+      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (long)key * p.d + (ch % DG) * 8);
     }
     if (v_active) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         int key = kv0 + v_kg * 4 + r;
         key = key < T ? key : T - 1;
-        rv[r] = *reinterpret_cast<const uint4*>(vbase + (long)key * p.d + v_dg * 8);
+        rv[r] = *reinterpret_cast<const u32x4*>(vbase + (long)key * p.d + v_dg * 8);
       }
     }
   };
-  auto store_lds = [&]() {
+  auto store_lds = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < K_CH; ++i) {
       const int ch = tid + i * 256;
-      *reinterpret_cast<uint4*>(&Ks[(ch / DG) * K_LD + (ch % DG) * 8]) = rk[i];
+      *reinterpret_cast<u32x4*>(&Ks[(ch / DG) * K_LD + (ch % DG) * 8]) = rk[i];
     }
     if (v_active) {
-      const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&rv[0]);
-      const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&rv[1]);
-      const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&rv[2]);
-      const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&rv[3]);
+      const u32x4 w0 = rv[0], w1 = rv[1], w2 = rv[2], w3 = rv[3];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         // channels 2e (low halves) and 2e+1 (high halves) of the 4 keys
-        uint2 lo, hi;
-        lo.x = (w0[e] & 0xffffu) | (w1[e] << 16);
-        lo.y = (w2[e] & 0xffffu) | (w3[e] << 16);
-        hi.x = (w0[e] >> 16) | (w1[e] & 0xffff0000u);
-        hi.y = (w2[e] >> 16) | (w3[e] & 0xffff0000u);
-        *reinterpret_cast<uint2*>(&Vt[(v_dg * 8 + 2 * e) * V_LD + v_kg * 4]) = lo;
-        *reinterpret_cast<uint2*>(&Vt[(v_dg * 8 + 2 * e + 1) * V_LD + v_kg * 4]) = hi;
+        u32x2 lo, hi;
+        lo[0] = (w0[e] & 0xffffu) | (w1[e] << 16);
+        lo[1] = (w2[e] & 0xffffu) | (w3[e] << 16);
+        hi[0] = (w0[e] >> 16) | (w1[e] & 0xffff0000u);
+        hi[1] = (w2[e] >> 16) | (w3[e] & 0xffff0000u);
+        *reinterpret_cast<u32x2*>(&Vt[(v_dg * 8 + 2 * e) * V_LD + v_kg * 4]) = lo;
+        *reinterpret_cast<u32x2*>(&Vt[(v_dg * 8 + 2 * e + 1) * V_LD + v_kg * 4]) = hi;
       }
     }
   };
@@ -131,7 +129,9 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnDev p) {
   for (int kv0 = 0; kv0 < T; kv0 += BKV) {
     store_lds();
     __syncthreads();
-    if (kv0 + BKV < T) load_global(kv0 + BKV);
+    // prefetch the next tile; past the end the last tile is fetched again (unused),
+    // which keeps the loop body free of a conditional around the staged registers
+    load_global(kv0 + BKV < T ? kv0 + BKV : kv0);
 
     // S^T tile: 64 keys x 32 query rows, as two 32-key MFMA tiles
     f32x16 acc_s[2];

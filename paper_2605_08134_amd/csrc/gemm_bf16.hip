@@ -4,22 +4,44 @@
 // and output projections, for all rows or only for the refreshed rows).
 //
 // Layout: A rows are k-contiguous; the weight arrives packed as Wt[n, k]
-// (k-contiguous), so both MFMA operands are 16-byte loads of 8 consecutive k.
-// A workgroup owns a BM x BN output tile and walks k in steps of 64 through a
-// double-buffered LDS stage (rows padded to 72 elements: conflict-free 16-byte
-// reads).  Each wave computes the TRANSPOSED tile with v_mfma_f32_32x32x16_bf16
-// (weight fragment as the first operand): a lane then owns one output row and
-// runs of 4 consecutive output columns, which gives 8-byte stores and keeps a
-// row's values inside one lane for row reductions.
-// Workgroup ids are remapped so that the ids the hardware deals round-robin to
-// the 8 XCDs become contiguous tile ranges per XCD (each XCD has its own L2).
+// (k-contiguous), so both MFMA operands are 16-byte runs of 8 consecutive k.
+//
+// A workgroup owns a BM x BN output tile and walks k in steps of 64.  Tiles of A
+// and Wt go from global memory STRAIGHT INTO LDS (global_load_lds_dwordx4: lane L
+// of a wave deposits its 16 bytes at wave_base + 16 L), through a ring of STAGES
+// buffers, so several k-steps are in flight while the matrix cores work on the
+// oldest one; no staging registers, no ds_write.  Because the LDS position is
+// fixed by the lane number, bank conflicts are removed on the global side: the
+// lane that owns LDS slot s of row r fetches k-chunk s ^ ((r >> 1) & 7), and the
+// MFMA fragment reads apply the same XOR (measured conflict-free for 16-byte
+// reads: 246 of 256 B/clk/CU).
+//
+// Each wave computes the TRANSPOSED tile with v_mfma_f32_32x32x16_bf16 (weight
+// fragment as the first operand): a lane then owns one output row and runs of 4
+// consecutive output columns, which gives 8-byte stores and keeps a row's values
+// inside one lane.
+//
+// Tile order.  The hardware deals workgroup ids round-robin to the 8 XCDs, each
+// with its own L2.  Ids are remapped so that every XCD works on a contiguous
+// range of tiles, and inside the range tiles run down groups of 8 row-tiles
+// before moving to the next column-tile: the workgroups that are resident on an
+// XCD at the same time then share both their A tiles and their weight tiles.
+//
+// Row count known only on the device (the refreshed-row list): one kernel holds
+// several tile shapes and every workgroup picks the same one from the count it
+// reads, so a step with 50 refreshed rows does not pay for a 256-row tile and no
+// host round trip is needed.  The grid is sized for the worst case; workgroups
+// beyond the tiles that exist return at once.
+#include <cstdlib>
+
 #include "dare_common.h"
 
 namespace dare {
 namespace {
 
-constexpr int BK = 64;
-constexpr int LDS_LD = BK + 8;  // padded row, in elements
+constexpr int BK = 64;            // k per stage: one 128-byte row segment
+constexpr int ROW_BYTES = BK * 2;
+constexpr int GROUP_M = 8;        // row-tiles walked before the next column-tile
 
 struct GemmDev {
   const bf16_t* a;
@@ -31,74 +53,93 @@ struct GemmDev {
   bf16_t* c2;
   float* c32;
   int lda, n, k, m_max, ldc, seg_n, c32_cols;
-  int tiles_m, tiles_n, per_xcd;
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-__global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
-    gemm_bf16_kernel(GemmDev p) {
-  constexpr int NT = WAVES_M * WAVES_N * 64;
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Wait until at most N of this wave's vector-memory operations are outstanding
+// and all of its LDS reads have returned, then join the workgroup barrier.
+// Written as one asm statement with a memory clobber: __syncthreads() would add a
+// release fence, and the compiler answers a fence with vmcnt(0), which would
+// drain the whole ring of in-flight k-steps.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_and_barrier() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int STAGES>
+constexpr int smem_bytes() {
+  return STAGES * (BM + BN) * ROW_BYTES;
+}
+
+// One output tile of C for m rows.  All threads of the workgroup call it with the
+// same arguments; smem holds at least smem_bytes<BM, BN, STAGES>() bytes.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+__device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigned char* smem) {
+  constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  constexpr int GROUPS = (BM + BN) / 8;  // 8-row groups = one wave load each
+  constexpr int LPW = GROUPS / NW;       // loads per wave per stage
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32 x 32");
+  static_assert(GROUPS % NW == 0, "row groups must divide among the waves");
+  static_assert(LPW * (STAGES - 1) < 64, "vmcnt range");
 
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_LD];
-
-  // XCD-aware tile order: hardware id -> (xcd, slot) -> contiguous range per XCD.
-  const int hw = blockIdx.x;
-  const int logical = (hw & 7) * p.per_xcd + (hw >> 3);
-  const int total = p.tiles_m * p.tiles_n;
+  // ---- which tile: XCD-contiguous ranges, GROUP_M row-tiles per column step ----
+  const int tiles_m = (m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) >> 3;
+  const int slot = blockIdx.x >> 3;
+  if (slot >= per_xcd) return;
+  const int logical = (blockIdx.x & 7) * per_xcd + slot;
   if (logical >= total) return;
-  const int tile_m = logical % p.tiles_m;  // m fastest: neighbours share a weight tile
-  const int tile_n = logical / p.tiles_m;
-  const int m = p.m_dev ? *p.m_dev : p.m_max;
+  const int group_size = GROUP_M * tiles_n;
+  const int first_m = (logical / group_size) * GROUP_M;
+  const int rows_in_group = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+  const int rem = logical % group_size;
+  const int tile_m = first_m + rem % rows_in_group;
+  const int tile_n = rem / rows_in_group;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-  if (m0 >= m) return;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
   const int l32 = lane & 31, half = lane >> 5;
 
-  // global -> register staging pointers
-  const bf16_t* a_src[A_CH];
-  const bf16_t* b_src[B_CH];
+  // ---- global -> LDS assignment: wave w issues loads for row groups w*LPW .. +LPW
+  // (rows 0..BM-1 are A rows, BM..BM+BN-1 are weight rows).  Lane L of a load owns
+  // row (L >> 3) of the group and LDS slot (L & 7); it fetches the k-chunk that
+  // the swizzle puts into that slot.  Rows past the end re-read the last row.
+  const bf16_t* src[LPW];
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int ch = tid + i * NT;
-    int row = m0 + (ch >> 3);
-    row = row < m ? row : m - 1;
-    const long tok = p.idx ? (long)p.idx[row] : (long)row;
-    a_src[i] = p.a + tok * p.lda + (ch & 7) * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int ch = tid + i * NT;
-    int col = n0 + (ch >> 3);
-    col = col < p.n ? col : p.n - 1;
-    b_src[i] = p.wt + (long)col * p.k + (ch & 7) * 8;
-  }
-
-  uint4 ra[A_CH], rb[B_CH];
-  auto load_global = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_src[i] + kt * BK);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + kt * BK);
-  };
-  auto store_lds = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int ch = tid + i * NT;
-      *reinterpret_cast<uint4*>(&As[buf][(ch >> 3) * LDS_LD + (ch & 7) * 8]) = ra[i];
+  for (int i = 0; i < LPW; ++i) {
+    const int r = (wave * LPW + i) * 8 + (lane >> 3);  // row within the stage
+    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+    if (r < BM) {
+      int row = m0 + r;
+      row = row < m ? row : m - 1;
+      const long tok = p.idx ? (long)p.idx[row] : (long)row;
+      src[i] = p.a + tok * p.lda + chunk * 8;
+    } else {
+      int col = n0 + (r - BM);
+      col = col < p.n ? col : p.n - 1;
+      src[i] = p.wt + (long)col * p.k + chunk * 8;
     }
+  }
+  auto issue_loads = [&](int kt, int buf) __attribute__((always_inline)) {
+    unsigned char* base = smem + buf * STAGE_BYTES + wave * LPW * 8 * ROW_BYTES;
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int ch = tid + i * NT;
-      *reinterpret_cast<uint4*>(&Bs[buf][(ch >> 3) * LDS_LD + (ch & 7) * 8]) = rb[i];
-    }
+    for (int i = 0; i < LPW; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + kt * BK),
+                                       (lptr_t)(base + i * 8 * ROW_BYTES), 16, 0, 0);
   };
 
   f32x16 acc[TM][TN];
@@ -109,33 +150,80 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int KT = p.k / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) load_global(kt + 1);
-    const bf16_t* as = &As[buf][(wave_m * WM + l32) * LDS_LD + half * 8];
-    const bf16_t* bs = &Bs[buf][(wave_n * WN + l32) * LDS_LD + half * 8];
+  // fragment read offsets: row (wave tile base + 32 i + l32), k-chunk 2 ks + half,
+  // stored at slot chunk ^ ((row >> 1) & 7); the tile bases are multiples of 32,
+  // so the XOR term depends on l32 only
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "fragment double buffering assumes an even slice count");
+  const int sw = (l32 >> 1) & 7;
+  int koff[KS];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = ((ks * 2 + half) ^ sw) * 16;
+  const int a_row_off = (wave_m * WM + l32) * ROW_BYTES;
+  const int b_row_off = (BM + wave_n * WN + l32) * ROW_BYTES;
+
+  // MFMA operands are double-buffered in registers: while the matrix cores work on
+  // k-slice ks, the fragments of k-slice ks+1 are already being read from LDS.
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto load_frags = [&](int buf, int ks, int set) __attribute__((always_inline)) {
+    const unsigned char* st = smem + buf * STAGE_BYTES;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDS_LD + ks * 16);
+    for (int i = 0; i < TM; ++i)
+      fa[set][i] = *reinterpret_cast<const bf16x8*>(st + a_row_off + i * 32 * ROW_BYTES + koff[ks]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDS_LD + ks * 16);
+    for (int j = 0; j < TN; ++j)
+      fb[set][j] = *reinterpret_cast<const bf16x8*>(st + b_row_off + j * 32 * ROW_BYTES + koff[ks]);
+  };
+  // MFMAs [first, last) of the TM x TN grid of one k-slice
+  auto mma = [&](int set, int first, int last) __attribute__((always_inline)) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    for (int t = 0; t < TM * TN; ++t) {
+      if (t < first || t >= last) continue;
+      const int i = t / TN, j = t % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < KT) store_lds(buf ^ 1);
-    __syncthreads();
+  };
+  // The LDS reads of the next k-slice are issued after the first PRE MFMAs of the
+  // current one and have the rest of the slice's MFMAs to complete under.
+  constexpr int PRE = TM * TN >= 8 ? 2 : 1;
+
+  // ---- pipeline: STAGES-1 k-steps in flight ahead of the one being multiplied.
+  // Loads of k-steps past the end are issued on the last valid k-step again (into
+  // a buffer nobody reads any more), so the count of outstanding loads per wave is
+  // the same in every iteration and one vmcnt value serves the whole loop.
+  // The barrier that publishes k-step kt+1 sits inside the last k-slice of k-step
+  // kt: by then every LDS read of k-step kt has been issued and (lgkmcnt 0) has
+  // completed, so the buffer may be refilled right after, and the first fragments
+  // of k-step kt+1 are fetched under the remaining MFMAs of that slice.
+  // The scheduling fences keep the compiler from sinking the LDS reads back down
+  // to their first use, which would undo the register double buffering.
+  const int KT = p.k / BK;
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) issue_loads(s < KT ? s : KT - 1, s);
+  wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
+  load_frags(0, 0, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt % STAGES;
+    const int nxt = kt + STAGES - 1;
+    issue_loads(nxt < KT ? nxt : KT - 1, nxt % STAGES);
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      mma(ks & 1, 0, PRE);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(buf, ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(ks & 1, PRE, TM * TN);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mma((KS - 1) & 1, 0, PRE);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
+    load_frags((kt + 1) % STAGES, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma((KS - 1) & 1, PRE, TM * TN);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  wait_vmcnt<0>();
 
   // Epilogue.  acc[i][j][r] = C[row, col] with
   //   row = m0 + wave_m*WM + i*32 + l32
@@ -172,8 +260,34 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
+// ---- one tile shape, chosen on the host (row count known or bounded) --------------
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+__global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDev p) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[smem_bytes<BM, BN, STAGES>()];
+  const int m = p.m_dev ? *p.m_dev : p.m_max;
+  if (m <= 0) return;
+  gemm_tile<BM, BN, WAVES_M, WAVES_N, STAGES>(p, m, smem);
+}
+
+// ---- row count read on the device: the tile shape follows it -------------------------
+constexpr int kRowsSmem = smem_bytes<256, 128, 3>();
+__global__ void __launch_bounds__(256) gemm_bf16_rows_kernel(GemmDev p) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kRowsSmem];
+  static_assert(smem_bytes<64, 64, 4>() <= kRowsSmem && smem_bytes<128, 64, 4>() <= kRowsSmem &&
+                    smem_bytes<256, 64, 3>() <= kRowsSmem, "shared buffer too small");
+  const int m = p.m_dev ? *p.m_dev : p.m_max;
+  if (m <= 0) return;
+  if (m <= 64)
+    gemm_tile<64, 64, 2, 2, 4>(p, m, smem);
+  else if (m <= 128)
+    gemm_tile<128, 64, 4, 1, 4>(p, m, smem);
+  else if (m <= 256)
+    gemm_tile<256, 64, 4, 1, 3>(p, m, smem);
+  else
+    gemm_tile<256, 128, 2, 2, 3>(p, m, smem);
+}
+
+GemmDev to_dev(const GemmArgs& g) {
   GemmDev p;
   p.a = static_cast<const bf16_t*>(g.a);
   p.wt = static_cast<const bf16_t*>(g.wt);
@@ -190,21 +304,65 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
   p.ldc = g.ldc;
   p.seg_n = g.seg_n;
   p.c32_cols = g.c32_cols;
-  p.tiles_m = (g.m_max + BM - 1) / BM;
-  p.tiles_n = (g.n + BN - 1) / BN;
-  const int total = p.tiles_m * p.tiles_n;
-  p.per_xcd = (total + 7) / 8;
-  if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N>), dim3(p.per_xcd * 8),
-                     dim3(WAVES_M * WAVES_N * 64), 0, s, p);
+  return p;
+}
+
+int grid_for(int tiles) { return ((tiles + 7) / 8) * 8; }
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+hipError_t launch_fixed(const GemmArgs& g, hipStream_t s) {
+  const int tiles = ((g.m_max + BM - 1) / BM) * ((g.n + BN - 1) / BN);
+  if (tiles == 0) return hipSuccess;
+  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, STAGES>), dim3(grid_for(tiles)),
+                     dim3(WAVES_M * WAVES_N * 64), 0, s, to_dev(g));
+  return hipGetLastError();
+}
+
+hipError_t launch_rows(const GemmArgs& g, hipStream_t s) {
+  // worst case over the shapes the kernel may pick: 256-row tiles, 64 columns wide
+  const int tiles = ((g.m_max + 255) / 256) * ((g.n + 63) / 64);
+  if (tiles == 0) return hipSuccess;
+  hipLaunchKernelGGL(gemm_bf16_rows_kernel, dim3(grid_for(tiles)), dim3(256), 0, s, to_dev(g));
   return hipGetLastError();
 }
 
 }  // namespace
 
+// cfg: 0 = choose by shape; other values force one configuration (tuning aid).
+hipError_t launch_gemm_bf16_cfg(const GemmArgs& g, int cfg, hipStream_t s) {
+  switch (cfg) {
+    case 1: return launch_fixed<128, 128, 2, 2, 4>(g, s);
+    case 2: return launch_fixed<128, 128, 2, 2, 3>(g, s);
+    case 3: return launch_fixed<128, 128, 2, 2, 2>(g, s);
+    case 4: return launch_fixed<256, 256, 2, 4, 2>(g, s);
+    case 5: return launch_fixed<256, 128, 4, 2, 3>(g, s);
+    case 7: return launch_fixed<128, 64, 4, 1, 4>(g, s);
+    case 8: return launch_fixed<256, 128, 2, 2, 3>(g, s);
+    case 9: return launch_fixed<256, 192, 4, 2, 2>(g, s);
+    case 10: return launch_fixed<256, 192, 2, 2, 2>(g, s);
+    case 11: return launch_fixed<256, 64, 4, 1, 3>(g, s);
+    case 12: return launch_fixed<64, 64, 2, 2, 4>(g, s);
+    case 13: return launch_fixed<128, 128, 4, 2, 4>(g, s);
+    case 14: return launch_fixed<128, 256, 2, 4, 2>(g, s);
+    case 20: return launch_rows(g, s);
+    default: break;
+  }
+  if (g.m_dev) return launch_rows(g, s);
+  // Row count known on the host.  Measured on MI355X (256 CUs): 256 x 256 tiles have
+  // the least LDS-fill traffic per flop and win once they fill the chip; 256 x 192
+  // gives exactly 256 tiles for 1024 x 12288; 128 x 128 with 8 waves is the best
+  // shape when the larger ones would leave most CUs idle.
+  auto tiles = [&](int bm, int bn) { return ((g.m_max + bm - 1) / bm) * ((g.n + bn - 1) / bn); };
+  if (g.n % 256 == 0 && tiles(256, 256) >= 512) return launch_fixed<256, 256, 2, 4, 2>(g, s);
+  if (g.n % 192 == 0 && tiles(256, 192) >= 224) return launch_fixed<256, 192, 4, 2, 2>(g, s);
+  if (g.n % 256 == 0 && tiles(256, 256) >= 224) return launch_fixed<256, 256, 2, 4, 2>(g, s);
+  if (g.n % 128 == 0 && tiles(128, 128) >= 64) return launch_fixed<128, 128, 4, 2, 4>(g, s);
+  return launch_fixed<64, 64, 2, 2, 4>(g, s);
+}
+
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
-  if (g.n % 128 == 0) return launch_cfg<128, 128, 2, 2>(g, s);
-  return launch_cfg<128, 64, 4, 1>(g, s);
+  const char* e = getenv("DARE_GEMM_CFG");  // tuning aid: force one tile configuration
+  return launch_gemm_bf16_cfg(g, e ? atoi(e) : 0, s);
 }
 
 }  // namespace dare
