@@ -33,6 +33,7 @@
 // host round trip is needed.  The grid is sized for the worst case; workgroups
 // beyond the tiles that exist return at once.
 #include <cstdlib>
+#include <type_traits>
 
 #include "dare_common.h"
 
@@ -114,6 +115,8 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
   const int l32 = lane & 31, half = lane >> 5;
 
+  const int KT = p.k / BK;
+
   // ---- global -> LDS assignment: wave w issues loads for row groups w*LPW .. +LPW
   // (rows 0..BM-1 are A rows, BM..BM+BN-1 are weight rows).  Lane L of a load owns
   // row (L >> 3) of the group and LDS slot (L & 7); it fetches the k-chunk that
@@ -162,66 +165,95 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   const int a_row_off = (wave_m * WM + l32) * ROW_BYTES;
   const int b_row_off = (BM + wave_n * WN + l32) * ROW_BYTES;
 
-  // MFMA operands are double-buffered in registers: while the matrix cores work on
-  // k-slice ks, the fragments of k-slice ks+1 are already being read from LDS.
-  bf16x8 fa[2][TM], fb[2][TN];
-  auto load_frags = [&](int buf, int ks, int set) __attribute__((always_inline)) {
-    const unsigned char* st = smem + buf * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-      fa[set][i] = *reinterpret_cast<const bf16x8*>(st + a_row_off + i * 32 * ROW_BYTES + koff[ks]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-      fb[set][j] = *reinterpret_cast<const bf16x8*>(st + b_row_off + j * 32 * ROW_BYTES + koff[ks]);
-  };
-  // MFMAs [first, last) of the TM x TN grid of one k-slice
-  auto mma = [&](int set, int first, int last) __attribute__((always_inline)) {
-#pragma unroll
-    for (int t = 0; t < TM * TN; ++t) {
-      if (t < first || t >= last) continue;
-      const int i = t / TN, j = t % TN;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
-    }
-  };
-  // The LDS reads of the next k-slice are issued after the first PRE MFMAs of the
-  // current one and have the rest of the slice's MFMAs to complete under.
-  constexpr int PRE = TM * TN >= 8 ? 2 : 1;
-
   // ---- pipeline: STAGES-1 k-steps in flight ahead of the one being multiplied.
   // Loads of k-steps past the end are issued on the last valid k-step again (into
   // a buffer nobody reads any more), so the count of outstanding loads per wave is
   // the same in every iteration and one vmcnt value serves the whole loop.
-  // The barrier that publishes k-step kt+1 sits inside the last k-slice of k-step
-  // kt: by then every LDS read of k-step kt has been issued and (lgkmcnt 0) has
-  // completed, so the buffer may be refilled right after, and the first fragments
-  // of k-step kt+1 are fetched under the remaining MFMAs of that slice.
+  //
+  // MFMA operands are double-buffered in registers: the LDS reads of the next unit
+  // of work are issued after the first PRE MFMAs of the current one and complete
+  // under the rest.  The unit is a 16-wide k-slice for large wave tiles; for small
+  // wave tiles (few MFMAs per slice, so nothing to hide an LDS round trip behind)
+  // it is the whole k-step: all fragments of k-step kt+1 are fetched under the MFMAs
+  // of k-step kt.  The barrier that publishes k-step kt+1 sits right before that
+  // fetch: by then every LDS read of k-step kt has been issued and (lgkmcnt 0) has
+  // completed, so its buffer may be refilled after the barrier.
   // The scheduling fences keep the compiler from sinking the LDS reads back down
   // to their first use, which would undo the register double buffering.
-  const int KT = p.k / BK;
+  constexpr bool WHOLE = TM * TN <= 4;
+  constexpr int FS = WHOLE ? KS : 1;  // k-slices held per fragment set
+  bf16x8 fa[2][FS][TM], fb[2][FS][TN];
+  auto load_frags = [&](int buf, int ks, int set, int slot) __attribute__((always_inline)) {
+    const unsigned char* st = smem + buf * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      fa[set][slot][i] = *reinterpret_cast<const bf16x8*>(st + a_row_off + i * 32 * ROW_BYTES + koff[ks]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      fb[set][slot][j] = *reinterpret_cast<const bf16x8*>(st + b_row_off + j * 32 * ROW_BYTES + koff[ks]);
+  };
+  // MFMAs [first, last) of the FS x TM x TN grid of one fragment set
+  auto mma = [&](int set, int first, int last) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < FS * TM * TN; ++t) {
+      if (t < first || t >= last) continue;
+      const int slot = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][slot][j], fa[set][slot][i], acc[i][j], 0, 0, 0);
+    }
+  };
+  constexpr int NMMA = FS * TM * TN;
+  constexpr int PRE = NMMA >= 8 ? 2 : 1;
+
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s) issue_loads(s < KT ? s : KT - 1, s);
   wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
-  load_frags(0, 0, 0);
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt % STAGES;
-    const int nxt = kt + STAGES - 1;
-    issue_loads(nxt < KT ? nxt : KT - 1, nxt % STAGES);
+  if constexpr (WHOLE) {
 #pragma unroll
-    for (int ks = 0; ks < KS - 1; ++ks) {
-      mma(ks & 1, 0, PRE);
+    for (int ks = 0; ks < KS; ++ks) load_frags(0, ks, 0, ks);
+    // two k-steps per trip so that the fragment set index is a compile-time constant
+    // (a run-time index would push the fragment arrays out of registers)
+    auto kstep = [&](int kt, auto set_c) __attribute__((always_inline)) {
+      constexpr int SET = decltype(set_c)::value;
+      const int nxt = kt + STAGES - 1;
+      issue_loads(nxt < KT ? nxt : KT - 1, nxt % STAGES);
+      mma(SET, 0, PRE);
       __builtin_amdgcn_sched_barrier(0);
-      load_frags(buf, ks + 1, (ks + 1) & 1);
+      wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) load_frags((kt + 1) % STAGES, ks, SET ^ 1, ks);
       __builtin_amdgcn_sched_barrier(0);
-      mma(ks & 1, PRE, TM * TN);
+      mma(SET, PRE, NMMA);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt + 1 < KT; kt += 2) {
+      kstep(kt, std::integral_constant<int, 0>{});
+      kstep(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
+  } else {
+    load_frags(0, 0, 0, 0);
+    for (int kt = 0; kt < KT; ++kt) {
+      const int buf = kt % STAGES;
+      const int nxt = kt + STAGES - 1;
+      issue_loads(nxt < KT ? nxt : KT - 1, nxt % STAGES);
+#pragma unroll
+      for (int ks = 0; ks < KS - 1; ++ks) {
+        mma(ks & 1, 0, PRE);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(buf, ks + 1, (ks + 1) & 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(ks & 1, PRE, NMMA);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      mma((KS - 1) & 1, 0, PRE);
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
+      load_frags((kt + 1) % STAGES, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      mma((KS - 1) & 1, PRE, NMMA);
       __builtin_amdgcn_sched_barrier(0);
     }
-    mma((KS - 1) & 1, 0, PRE);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
-    load_frags((kt + 1) % STAGES, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma((KS - 1) & 1, PRE, TM * TN);
-    __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();
 
@@ -270,21 +302,20 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDe
 }
 
 // ---- row count read on the device: the tile shape follows it -------------------------
-constexpr int kRowsSmem = smem_bytes<256, 128, 3>();
+constexpr int kRowsSmem = smem_bytes<64, 64, 4>();  // 64 KiB: two workgroups per CU
 __global__ void __launch_bounds__(256) gemm_bf16_rows_kernel(GemmDev p) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kRowsSmem];
-  static_assert(smem_bytes<64, 64, 4>() <= kRowsSmem && smem_bytes<128, 64, 4>() <= kRowsSmem &&
-                    smem_bytes<256, 64, 3>() <= kRowsSmem, "shared buffer too small");
+  static_assert(smem_bytes<128, 128, 2>() <= kRowsSmem, "shared buffer too small");
   const int m = p.m_dev ? *p.m_dev : p.m_max;
   if (m <= 0) return;
-  if (m <= 64)
+  // Up to 256 rows the projection is a stream over the weight matrix and what
+  // matters is the number of workgroups pulling on it: 64 x 64 tiles (measured best
+  // for 52..256 rows at n = 4096 and n = 12288).  Beyond that, 128 x 128 tiles with a
+  // two-stage ring, which fit the same 64 KiB.
+  if (m <= 256)
     gemm_tile<64, 64, 2, 2, 4>(p, m, smem);
-  else if (m <= 128)
-    gemm_tile<128, 64, 4, 1, 4>(p, m, smem);
-  else if (m <= 256)
-    gemm_tile<256, 64, 4, 1, 3>(p, m, smem);
   else
-    gemm_tile<256, 128, 2, 2, 3>(p, m, smem);
+    gemm_tile<128, 128, 2, 2, 2>(p, m, smem);
 }
 
 GemmDev to_dev(const GemmArgs& g) {
@@ -319,8 +350,11 @@ hipError_t launch_fixed(const GemmArgs& g, hipStream_t s) {
 }
 
 hipError_t launch_rows(const GemmArgs& g, hipStream_t s) {
-  // worst case over the shapes the kernel may pick: 256-row tiles, 64 columns wide
-  const int tiles = ((g.m_max + 255) / 256) * ((g.n + 63) / 64);
+  // worst case over the shapes the kernel may pick
+  const int small = 4 * ((g.n + 63) / 64);                           // <= 256 rows, 64 x 64
+  const int large = ((g.m_max + 127) / 128) * ((g.n + 127) / 128);  // 128 x 128
+  const int tiles = g.m_max <= 256 ? ((g.m_max + 63) / 64) * ((g.n + 63) / 64)
+                                   : (small > large ? small : large);
   if (tiles == 0) return hipSuccess;
   hipLaunchKernelGGL(gemm_bf16_rows_kernel, dim3(grid_for(tiles)), dim3(256), 0, s, to_dev(g));
   return hipGetLastError();
