@@ -39,25 +39,33 @@ dare_status dare_k_pack_weight(int dtype, const void* w, int rows_k, int cols_n,
  *        columns [0, c32_cols), taken from the fp32 accumulators before rounding
  *        to dtype: the input of the drift score.  c may be all NULL when only
  *        c32 is wanted (then n == c32_cols).
+ *   k_parts  1, or (bf16, all rows, c all NULL, c32_cols == n) a divisor of k/64: k is
+ *        cut into k_parts ranges computed by separate workgroups, and range s writes
+ *        its partial products to c32 + s * c32_part_stride (elements).  The sum over s,
+ *        taken in order, is the projection; dare_k_score adds the slabs itself.  Meant
+ *        for the scored query columns of all rows (few output tiles, long k).
  * k must be a multiple of 64, n of 64 (bf16) / 16 (fp32).
  */
 dare_status dare_k_gemm(int dtype, const void* a, int lda, const void* wt, int n,
                         int k, int m_max, const int32_t* idx,
                         const int32_t* m_dev, void* const* c, int ldc, int seg_n,
-                        float* c32, int c32_cols, void* hip_stream);
+                        float* c32, int c32_cols, int k_parts, long c32_part_stride,
+                        void* hip_stream);
 
 /*
  * Drift score and reuse decision (Sec. 3.1 eq. 1, Sec. 3.2 eq. 2; Alg. 1/2
  * lines 3-5) for n_tokens tokens:
  *   s = 1 - <q, p> / max(sqrt(|q|^2 |p|^2), 1e-30), q = q_new[t, 0:width],
  *   p = q_prev[t, 0:width]; mask = (s <= threshold) unless force_refresh;
- *   then q_prev[t] = q_new[t].
- *   q_new [n_tokens, ld_new] fp32; q_prev [n_tokens, width] fp32 in/out;
+ *   then q_prev[t] = q.
+ *   q_new [n_tokens, ld_new] fp32, or n_parts such slabs part_stride elements apart
+ *   whose sum (taken in slab order) is q; q_prev [n_tokens, width] fp32 in/out;
  *   scores optional [n_tokens] fp32; mask [n_tokens] bytes.
  */
-dare_status dare_k_score(const float* q_new, int ld_new, int width, float* q_prev,
-                         int n_tokens, float threshold, int force_refresh,
-                         float* scores, uint8_t* mask, void* hip_stream);
+dare_status dare_k_score(const float* q_new, int ld_new, int width, int n_parts,
+                         long part_stride, float* q_prev, int n_tokens,
+                         float threshold, int force_refresh, float* scores,
+                         uint8_t* mask, void* hip_stream);
 
 /*
  * Ordered compaction of the refreshed set (Alg. 1/2 line 5): sel_idx = ascending

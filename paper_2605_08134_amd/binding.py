@@ -70,9 +70,9 @@ def lib():
     L.dare_k_pack_weight.argtypes = [i32, vp, i32, i32, vp, i32, vp]
     L.dare_k_pack_weight.restype = i32
     L.dare_k_gemm.argtypes = [i32, vp, i32, vp, i32, i32, i32, vp, vp, ctypes.POINTER(vp), i32, i32,
-                              vp, i32, vp]
+                              vp, i32, i32, ctypes.c_long, vp]
     L.dare_k_gemm.restype = i32
-    L.dare_k_score.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp]
+    L.dare_k_score.argtypes = [vp, i32, i32, i32, ctypes.c_long, vp, i32, f32, i32, vp, vp, vp]
     L.dare_k_score.restype = i32
     L.dare_k_compact.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     L.dare_k_compact.restype = i32
@@ -178,7 +178,7 @@ def dare_k_pack_weight(w, stream=None):
     return wt
 
 
-def dare_k_gemm(a, wt, outs, seg_n, idx=None, m_dev=None, m_max=None, c32=None, stream=None):
+def dare_k_gemm(a, wt, outs, seg_n, idx=None, m_dev=None, m_max=None, c32=None, k_parts=1, stream=None):
     import torch
     n, k = wt.shape
     dtype = DARE_BF16 if a.dtype == torch.bfloat16 else DARE_F32
@@ -188,12 +188,13 @@ def dare_k_gemm(a, wt, outs, seg_n, idx=None, m_dev=None, m_max=None, c32=None, 
         m_max = a.shape[0] if idx is None else idx.shape[0]
     _check(lib().dare_k_gemm(dtype, _ptr(a), a.shape[-1], _ptr(wt), n, k, m_max, _ptr(idx), _ptr(m_dev),
                              arr, ldc, seg_n, _ptr(c32), 0 if c32 is None else c32.shape[-1],
-                             _stream(stream)))
+                             k_parts, 0 if c32 is None else m_max * c32.shape[-1], _stream(stream)))
 
 
-def dare_k_score(q_new, q_prev, threshold, force_refresh, scores, mask, stream=None):
+def dare_k_score(q_new, q_prev, threshold, force_refresh, scores, mask, n_parts=1, stream=None):
     n_tokens, width = q_prev.shape[0], q_prev.shape[-1]
-    _check(lib().dare_k_score(_ptr(q_new), q_new.shape[-1], width, _ptr(q_prev), n_tokens, threshold,
+    _check(lib().dare_k_score(_ptr(q_new), q_new.shape[-1], width, n_parts, n_tokens * q_new.shape[-1],
+                              _ptr(q_prev), n_tokens, threshold,
                               int(force_refresh), _ptr(scores), _ptr(mask), _stream(stream)))
 
 

@@ -19,7 +19,9 @@ struct dare_ctx {
   void* wo_t;          // [d, d] packed Wo
   void* q_buf;         // [max tokens, d] queries, token-indexed
   void* attn_buf;      // [max tokens, d] attention rows before Wo, token-indexed
-  float* q_new;        // [max tokens, score_width] fp32 scored query of this step
+  float* q_new;        // fp32 scored query of this step: up to 8 k-range slabs of
+                       // [tokens, score_width]
+  size_t q_new_elems;
   int32_t* sel_idx;    // [max tokens]
   int32_t* sel_off;    // [max_batch + 1]
   void* attn_work;
@@ -124,12 +126,16 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, 
   c->attn_work_bytes = cfg->dtype == DARE_BF16
                            ? attn_bf16_work_bytes(cfg->max_batch, cfg->max_seq, cfg->n_heads, cfg->head_dim)
                            : 0;
+  // room for 8 k-range slabs of the scored columns up to 4096 tokens (beyond that the
+  // projection has enough tiles without cutting k)
+  c->q_new_elems = (size_t)max_tok * c->score_width;
+  if (max_tok <= 4096) c->q_new_elems *= 8;
   struct { void** p; size_t bytes; } allocs[] = {
       {&c->wqkv_t, 3 * d * d * c->esize},
       {&c->wo_t, d * d * c->esize},
       {&c->q_buf, (size_t)max_tok * d * c->esize},
       {&c->attn_buf, (size_t)max_tok * d * c->esize},
-      {(void**)&c->q_new, (size_t)max_tok * c->score_width * sizeof(float)},
+      {(void**)&c->q_new, c->q_new_elems * sizeof(float)},
       {(void**)&c->sel_idx, (size_t)max_tok * sizeof(int32_t)},
       {(void**)&c->sel_off, ((size_t)cfg->max_batch + 1) * sizeof(int32_t)},
       {&c->attn_work, (size_t)c->attn_work_bytes},
@@ -192,6 +198,7 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
   const bool sel_o = mode == DARE_MODE_O || mode == DARE_MODE_KVO;
   const int32_t* n_sel = ctx->sel_off + batch;  // device count of refreshed tokens
   hipError_t e;
+  int k_parts = 1;
 
   // 1. Query projection feeding the score (Alg. 1/2 line 2), together with whatever
   //    else this mode projects for all rows.
@@ -215,11 +222,21 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
     g.c[0] = ctx->q_buf;
   } else {
     g.n = sw;  // only the scored columns of Q for every row
+    // few output tiles, long k: cut k into ranges that the score kernel adds up
+    if (cf.dtype == DARE_BF16) {
+      const int tiles = ((n_tok + 63) / 64) * ((sw + 63) / 64), ksteps = d / 64;
+      while (tiles * k_parts * 2 <= 256 && k_parts * 2 <= 8 && ksteps % (k_parts * 2) == 0 &&
+             ksteps / (k_parts * 2) >= 4 && (size_t)n_tok * sw * (k_parts * 2) <= ctx->q_new_elems)
+        k_parts *= 2;
+      g.k_parts = k_parts;
+      g.c32_part_stride = (long)n_tok * sw;
+    }
   }
   if ((e = gemm(ctx, g, s)) != hipSuccess) return fail_hip(ctx, e, "query projection");
 
   // 2. Drift score, reuse decision, score-cache update (Alg. 1/2 lines 3-5).
-  e = launch_score(ctx->q_new, sw, sw, q_prev, n_tok, threshold, mode == DARE_MODE_DENSE, scores,
+  e = launch_score(ctx->q_new, sw, sw, k_parts, (long)n_tok * sw, q_prev, n_tok, threshold,
+                   mode == DARE_MODE_DENSE, scores,
                    nullptr, reuse_mask, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "score");
 
@@ -314,12 +331,18 @@ dare_status dare_k_pack_weight(int dtype, const void* w, int rows_k, int cols_n,
 
 dare_status dare_k_gemm(int dtype, const void* a, int lda, const void* wt, int n, int k, int m_max,
                         const int32_t* idx, const int32_t* m_dev, void* const* c, int ldc, int seg_n,
-                        float* c32, int c32_cols, void* hip_stream) {
+                        float* c32, int c32_cols, int k_parts, long c32_part_stride, void* hip_stream) {
   if (!a || !wt || !c || n < 1 || k < 1 || m_max < 0 || lda < k) return DARE_ERR_INVALID_ARG;
   if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
   if (seg_n < 1 || n % seg_n != 0 || n / seg_n > 3) return DARE_ERR_INVALID_ARG;
   if (c32 && (c32_cols < 1 || c32_cols > n || c32_cols % 4 != 0)) return DARE_ERR_INVALID_ARG;
   if (k % 64 != 0 || n % (dtype == DARE_BF16 ? 64 : 16) != 0 || seg_n % 4 != 0) return DARE_ERR_UNSUPPORTED;
+  if (k_parts < 1) return DARE_ERR_INVALID_ARG;
+  if (k_parts > 1) {
+    if (!c32 || c32_cols != n || c[0] || idx || m_dev || c32_part_stride < (long)m_max * c32_cols)
+      return DARE_ERR_INVALID_ARG;
+    if (dtype != DARE_BF16 || (k / 64) % k_parts != 0) return DARE_ERR_UNSUPPORTED;
+  }
   GemmArgs g{};
   g.a = a;
   g.lda = lda;
@@ -334,17 +357,21 @@ dare_status dare_k_gemm(int dtype, const void* a, int lda, const void* wt, int n
   g.seg_n = seg_n;
   g.c32 = c32;
   g.c32_cols = c32 ? c32_cols : 0;
+  g.k_parts = k_parts;
+  g.c32_part_stride = c32_part_stride;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e = dtype == DARE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }
 
-dare_status dare_k_score(const float* q_new, int ld_new, int width, float* q_prev, int n_tokens,
-                         float threshold, int force_refresh, float* scores, uint8_t* mask,
-                         void* hip_stream) {
+dare_status dare_k_score(const float* q_new, int ld_new, int width, int n_parts, long part_stride,
+                         float* q_prev, int n_tokens, float threshold, int force_refresh,
+                         float* scores, uint8_t* mask, void* hip_stream) {
   if (!q_new || !q_prev || !mask || width < 1 || ld_new < width || n_tokens < 0 || std::isnan(threshold))
     return DARE_ERR_INVALID_ARG;
-  hipError_t e = launch_score(q_new, ld_new, width, q_prev, n_tokens, threshold, force_refresh, scores,
+  if (n_parts < 1 || (n_parts > 1 && part_stride < (long)n_tokens * ld_new)) return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_score(q_new, ld_new, width, n_parts, part_stride, q_prev, n_tokens, threshold,
+                              force_refresh, scores,
                               nullptr, mask, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }

@@ -36,6 +36,8 @@ struct GemmArgs {
   int seg_n;
   float* c32;         // optional fp32 copy of columns [0, c32_cols)
   int c32_cols;
+  int k_parts;        // > 1: only c32 is written, as k_parts slabs of partial sums
+  long c32_part_stride;
 };
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
@@ -57,8 +59,8 @@ uint64_t attn_bf16_work_bytes(int batch, int seq, int n_heads, int head_dim);
 
 hipError_t launch_pack_weight(int dtype, const void* w, int rows_k, int cols_n, void* wt,
                               int ldwt, hipStream_t s);
-hipError_t launch_score(const float* q_new, int ld_new, int width, float* q_prev, int n_tokens,
-                        float threshold, int force_refresh, float* scores, float* scores2,
+hipError_t launch_score(const float* q_new, int ld_new, int width, int n_parts, long part_stride,
+                        float* q_prev, int n_tokens, float threshold, int force_refresh, float* scores, float* scores2,
                         uint8_t* mask, hipStream_t s);
 hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_idx,
                           int32_t* sel_idx2, int32_t* sel_count, int32_t* sel_count2,

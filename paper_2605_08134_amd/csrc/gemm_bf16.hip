@@ -21,6 +21,12 @@
 // consecutive output columns, which gives 8-byte stores and keeps a row's values
 // inside one lane.
 //
+// k-parts.  A projection with few output tiles and a long k (the scored query columns
+// for all rows: 1024 x 128 x 4096) can cut k into ranges that run as separate
+// workgroups; each range writes its fp32 partial products to its own slab of the fp32
+// output and the consumer (the score kernel) adds the slabs in range order.  No
+// atomics, no fences: the kernel boundary orders producer and consumer.
+//
 // Tile order.  The hardware deals workgroup ids round-robin to the 8 XCDs, each
 // with its own L2.  Ids are remapped so that every XCD works on a contiguous
 // range of tiles, and inside the range tiles run down groups of 8 row-tiles
@@ -54,6 +60,8 @@ struct GemmDev {
   bf16_t* c2;
   float* c32;
   int lda, n, k, m_max, ldc, seg_n, c32_cols;
+  int k_parts;           // k is cut into this many ranges (1 = whole k per tile)
+  long c32_part_stride;  // elements between the fp32 outputs of consecutive ranges
 };
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -95,13 +103,16 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   static_assert(LPW * (STAGES - 1) < 64, "vmcnt range");
 
   // ---- which tile: XCD-contiguous ranges, GROUP_M row-tiles per column step ----
+  // (the k-ranges of one tile are neighbours in this order)
+  const int parts = p.k_parts;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
-  const int total = tiles_m * tiles_n;
+  const int total = tiles_m * tiles_n * parts;
   const int per_xcd = (total + 7) >> 3;
   const int slot = blockIdx.x >> 3;
   if (slot >= per_xcd) return;
-  const int logical = (blockIdx.x & 7) * per_xcd + slot;
-  if (logical >= total) return;
+  const int unit = (blockIdx.x & 7) * per_xcd + slot;
+  if (unit >= total) return;
+  const int logical = unit / parts, part = unit - logical * parts;
   const int group_size = GROUP_M * tiles_n;
   const int first_m = (logical / group_size) * GROUP_M;
   const int rows_in_group = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
@@ -115,7 +126,9 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
   const int l32 = lane & 31, half = lane >> 5;
 
-  const int KT = p.k / BK;
+  // this workgroup's k-range, in k-steps (the host makes parts divide the step count)
+  const int KT = p.k / BK / parts;
+  const int kt0 = part * KT;
 
   // ---- global -> LDS assignment: wave w issues loads for row groups w*LPW .. +LPW
   // (rows 0..BM-1 are A rows, BM..BM+BN-1 are weight rows).  Lane L of a load owns
@@ -130,11 +143,11 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
       int row = m0 + r;
       row = row < m ? row : m - 1;
       const long tok = p.idx ? (long)p.idx[row] : (long)row;
-      src[i] = p.a + tok * p.lda + chunk * 8;
+      src[i] = p.a + tok * p.lda + chunk * 8 + kt0 * BK;
     } else {
       int col = n0 + (r - BM);
       col = col < p.n ? col : p.n - 1;
-      src[i] = p.wt + (long)col * p.k + chunk * 8;
+      src[i] = p.wt + (long)col * p.k + chunk * 8 + kt0 * BK;
     }
   }
   auto issue_loads = [&](int kt, int buf) __attribute__((always_inline)) {
@@ -257,6 +270,7 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   }
   wait_vmcnt<0>();
 
+  float* c32 = p.c32 ? p.c32 + part * p.c32_part_stride : nullptr;
   // Epilogue.  acc[i][j][r] = C[row, col] with
   //   row = m0 + wave_m*WM + i*32 + l32
   //   col = n0 + wave_n*WN + j*32 + (r/4)*8 + half*4 + r%4
@@ -283,9 +297,9 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
           o[3] = (bf16_t)v3;
           *reinterpret_cast<bf16x4*>(cbase + tok * p.ldc + (col - seg * p.seg_n)) = o;
         }
-        if (p.c32 && col < p.c32_cols) {
+        if (c32 && col < p.c32_cols) {
           f32x4 o = {v0, v1, v2, v3};
-          *reinterpret_cast<f32x4*>(p.c32 + tok * p.c32_cols + col) = o;
+          *reinterpret_cast<f32x4*>(c32 + tok * p.c32_cols + col) = o;
         }
       }
     }
@@ -335,6 +349,8 @@ GemmDev to_dev(const GemmArgs& g) {
   p.ldc = g.ldc;
   p.seg_n = g.seg_n;
   p.c32_cols = g.c32_cols;
+  p.k_parts = 1;
+  p.c32_part_stride = 0;
   return p;
 }
 
@@ -344,8 +360,13 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 hipError_t launch_fixed(const GemmArgs& g, hipStream_t s) {
   const int tiles = ((g.m_max + BM - 1) / BM) * ((g.n + BN - 1) / BN);
   if (tiles == 0) return hipSuccess;
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, STAGES>), dim3(grid_for(tiles)),
-                     dim3(WAVES_M * WAVES_N * 64), 0, s, to_dev(g));
+  GemmDev p = to_dev(g);
+  if (g.k_parts > 1) {
+    p.k_parts = g.k_parts;
+    p.c32_part_stride = g.c32_part_stride;
+  }
+  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, STAGES>), dim3(grid_for(tiles * p.k_parts)),
+                     dim3(WAVES_M * WAVES_N * 64), 0, s, p);
   return hipGetLastError();
 }
 

@@ -40,7 +40,8 @@ __device__ inline float wave_sum(float v) {
 }
 
 __global__ void __launch_bounds__(256) score_kernel(const float* __restrict__ q_new, int ld_new,
-                                                   int width, float* __restrict__ q_prev,
+                                                   int width, int n_parts, long part_stride,
+                                                   float* __restrict__ q_prev,
                                                    int n_tokens, float threshold,
                                                    int force_refresh, float* __restrict__ scores,
                                                    float* __restrict__ scores2,
@@ -52,7 +53,9 @@ __global__ void __launch_bounds__(256) score_kernel(const float* __restrict__ q_
   float* p = q_prev + (long)tok * width;
   float dot = 0.f, nq = 0.f, np = 0.f;
   for (int c = lane; c < width; c += 64) {
-    const float a = q[c], b = p[c];
+    float a = q[c];
+    for (int s = 1; s < n_parts; ++s) a += q[c + s * part_stride];  // k-range slabs, in order
+    const float b = p[c];
     dot = fmaf(a, b, dot);
     nq = fmaf(a, a, nq);
     np = fmaf(b, b, np);
@@ -175,12 +178,12 @@ hipError_t launch_pack_weight(int dtype, const void* w, int rows_k, int cols_n, 
   return hipGetLastError();
 }
 
-hipError_t launch_score(const float* q_new, int ld_new, int width, float* q_prev, int n_tokens,
-                        float threshold, int force_refresh, float* scores, float* scores2,
+hipError_t launch_score(const float* q_new, int ld_new, int width, int n_parts, long part_stride,
+                        float* q_prev, int n_tokens, float threshold, int force_refresh, float* scores, float* scores2,
                         uint8_t* mask, hipStream_t s) {
   if (n_tokens == 0) return hipSuccess;
   hipLaunchKernelGGL(score_kernel, dim3((n_tokens + 3) / 4), dim3(256), 0, s, q_new, ld_new, width,
-                     q_prev, n_tokens, threshold, force_refresh, scores, scores2, mask);
+                     n_parts, part_stride, q_prev, n_tokens, threshold, force_refresh, scores, scores2, mask);
   return hipGetLastError();
 }
 

@@ -80,13 +80,17 @@ def test_step_and_destroy_null_context(L):
 def test_kernel_entry_points_reject_bad_arguments(L):
     f = 0x1000
     arr = (ctypes.c_void_p * 3)(f, None, None)
-    assert L.dare_k_gemm(B.DARE_BF16, None, 64, f, 64, 64, 1, None, None, arr, 64, 64, None, 0, None) == B.DARE_ERR_INVALID_ARG
-    assert L.dare_k_gemm(B.DARE_BF16, f, 32, f, 64, 64, 1, None, None, arr, 64, 64, None, 0, None) == B.DARE_ERR_INVALID_ARG
-    assert L.dare_k_gemm(B.DARE_BF16, f, 96, f, 64, 96, 1, None, None, arr, 64, 64, None, 0, None) == B.DARE_ERR_UNSUPPORTED
-    assert L.dare_k_gemm(5, f, 64, f, 64, 64, 1, None, None, arr, 64, 64, None, 0, None) == B.DARE_ERR_INVALID_ARG
-    assert L.dare_k_gemm(B.DARE_BF16, f, 64, f, 128, 64, 1, None, None, arr, 64, 48, None, 0, None) == B.DARE_ERR_INVALID_ARG
-    assert L.dare_k_score(f, 64, 64, f, 4, float("nan"), 0, None, f, None) == B.DARE_ERR_INVALID_ARG
-    assert L.dare_k_score(f, 32, 64, f, 4, 0.1, 0, None, f, None) == B.DARE_ERR_INVALID_ARG
+    assert L.dare_k_gemm(B.DARE_BF16, None, 64, f, 64, 64, 1, None, None, arr, 64, 64, None, 0, 1, 0, None) == B.DARE_ERR_INVALID_ARG
+    assert L.dare_k_gemm(B.DARE_BF16, f, 32, f, 64, 64, 1, None, None, arr, 64, 64, None, 0, 1, 0, None) == B.DARE_ERR_INVALID_ARG
+    assert L.dare_k_gemm(B.DARE_BF16, f, 96, f, 64, 96, 1, None, None, arr, 64, 64, None, 0, 1, 0, None) == B.DARE_ERR_UNSUPPORTED
+    assert L.dare_k_gemm(5, f, 64, f, 64, 64, 1, None, None, arr, 64, 64, None, 0, 1, 0, None) == B.DARE_ERR_INVALID_ARG
+    assert L.dare_k_gemm(B.DARE_BF16, f, 64, f, 128, 64, 1, None, None, arr, 64, 48, None, 0, 1, 0, None) == B.DARE_ERR_INVALID_ARG
+    assert L.dare_k_score(f, 64, 64, 1, 0, f, 4, float("nan"), 0, None, f, None) == B.DARE_ERR_INVALID_ARG
+    assert L.dare_k_score(f, 32, 64, 1, 0, f, 4, 0.1, 0, None, f, None) == B.DARE_ERR_INVALID_ARG
+    assert L.dare_k_score(f, 64, 64, 2, 8, f, 4, 0.1, 0, None, f, None) == B.DARE_ERR_INVALID_ARG
+    arr0 = (ctypes.c_void_p * 3)(None, None, None)
+    assert L.dare_k_gemm(B.DARE_BF16, f, 256, f, 64, 256, 8, None, None, arr0, 64, 64, f, 64, 3, 512, None) == B.DARE_ERR_UNSUPPORTED
+    assert L.dare_k_gemm(B.DARE_BF16, f, 256, f, 64, 256, 8, None, None, arr0, 64, 64, f, 64, 2, 100, None) == B.DARE_ERR_INVALID_ARG
     assert L.dare_k_compact(None, 1, 8, f, f, f, None) == B.DARE_ERR_INVALID_ARG
     assert L.dare_k_attention(B.DARE_BF16, f, f, f, f, 1, 8, 2, 96, None, None, None, 0, None) == B.DARE_ERR_UNSUPPORTED
     assert L.dare_k_attention(B.DARE_BF16, f, f, f, f, 1, 8, 2, 64, f, None, None, 0, None) == B.DARE_ERR_INVALID_ARG

@@ -81,6 +81,32 @@ def test_gemm_selected_rows_device_count(B, dtype, count):
         assert_close(got[rows], want[rows], dtype)
 
 
+def test_gemm_k_parts_feed_the_score(B):
+    # the scored-columns projection cut along k: slabs of partial sums that the score
+    # kernel adds up, against the uncut projection and the oracle's score
+    r = _rng(3)
+    m, k, n, parts = 1000, 2048, 128, 4
+    a = store(r.standard_normal((m, k)), "bf16")
+    w = store(r.standard_normal((k, n)) * 0.03, "bf16")
+    wt = B.dare_k_pack_weight(dev(w, "bf16"))
+    slabs = torch.full((parts, m, n), float("nan"), dtype=torch.float32, device="cuda")
+    B.dare_k_gemm(dev(a, "bf16"), wt, [None], n, m_max=m, c32=slabs, k_parts=parts)
+    torch.cuda.synchronize()
+    want = a.astype(np.float64) @ w.astype(np.float64)
+    assert rel_err(host(slabs).sum(axis=0), want) <= 2e-6
+    for s in range(parts):
+        ks = slice(s * k // parts, (s + 1) * k // parts)
+        assert rel_err(host(slabs[s]), a[:, ks].astype(np.float64) @ w[ks].astype(np.float64)) <= 2e-6
+    p = (want + 0.05 * r.standard_normal(want.shape)).astype(np.float32)
+    pd = dev(p)
+    scores = torch.zeros(m, dtype=torch.float32, device="cuda")
+    mask = torch.zeros(m, dtype=torch.uint8, device="cuda")
+    B.dare_k_score(slabs.view(parts * m, n), pd, 0.01, False, scores, mask, n_parts=parts)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(host(scores) - orc.drift_scores(want, p))) < 5e-7
+    assert rel_err(host(pd), want) <= 2e-6
+
+
 def test_score_kernel(B):
     r = _rng(9)
     n, w, ld = 333, 128, 160
