@@ -140,11 +140,18 @@ def main():
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": None,
+        "traffic": stored_traffic(),
         "us_per_launch": dom_ms * 1e3,
         "tflops": dom_flops / (dom_ms * 1e-3) / 1e12,
     }
     if args.only_dominant:
+        # profiler passes: the same launches plus a plain copy of known size, whose
+        # counter readings calibrate FETCH_SIZE / WRITE_SIZE (64 MiB read, 64 MiB written)
+        src = torch.ones((8192, d), dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            B.dare_k_copy_rows(src, dst)
+        torch.cuda.synchronize()
         print(json.dumps({"roofline": roofline}))
         return
 
@@ -214,6 +221,20 @@ def main():
         "sweep": sweep,
     }
     print(json.dumps(out))
+
+
+def stored_traffic():
+    """HBM bytes per launch of the dominant kernel, from the committed counter summary
+    (two rocprofv3 --pmc passes over `bench.py --only-dominant`, scaled by the copy
+    kernel of the same run); None when the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "gemm_rows_qkv_llada8b_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(weights, seed, cfg, tau):

@@ -88,10 +88,14 @@ constexpr int smem_bytes() {
   return STAGES * (BM + BN) * ROW_BYTES;
 }
 
-// One output tile of C for m rows.  All threads of the workgroup call it with the
-// same arguments; smem holds at least smem_bytes<BM, BN, STAGES>() bytes.
+// One output tile of C for m rows, computed by a team of WAVES_M * WAVES_N waves; tid
+// is the thread's index within the team and smem the team's own
+// smem_bytes<BM, BN, STAGES>() bytes.  A workgroup is one team (nsub = 1) or nsub teams
+// on neighbouring tiles (team number sub).  Teams share the workgroup barrier, so a
+// team without a tile of its own repeats the last tile and stores nothing.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
-__device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigned char* smem) {
+__device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigned char* smem,
+                                          const int tid, const int sub = 0, const int nsub = 1) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -103,15 +107,20 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   static_assert(LPW * (STAGES - 1) < 64, "vmcnt range");
 
   // ---- which tile: XCD-contiguous ranges, GROUP_M row-tiles per column step ----
-  // (the k-ranges of one tile are neighbours in this order)
+  // (the k-ranges of one tile, and the tiles of one workgroup's teams, are neighbours
+  // in this order)
   const int parts = p.k_parts;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
   const int total = tiles_m * tiles_n * parts;
-  const int per_xcd = (total + 7) >> 3;
+  const int blocks = (total + nsub - 1) / nsub;
+  const int per_xcd = (blocks + 7) >> 3;
   const int slot = blockIdx.x >> 3;
   if (slot >= per_xcd) return;
-  const int unit = (blockIdx.x & 7) * per_xcd + slot;
-  if (unit >= total) return;
+  const int blk = (blockIdx.x & 7) * per_xcd + slot;
+  if (blk >= blocks) return;
+  int unit = blk * nsub + sub;
+  const bool live = unit < total;
+  unit = live ? unit : total - 1;
   const int logical = unit / parts, part = unit - logical * parts;
   const int group_size = GROUP_M * tiles_n;
   const int first_m = (logical / group_size) * GROUP_M;
@@ -121,7 +130,6 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   const int tile_n = rem / rows_in_group;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
   const int l32 = lane & 31, half = lane >> 5;
@@ -277,7 +285,7 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + wave_m * WM + i * 32 + l32;
-    if (row >= m) continue;
+    if (row >= m || !live) continue;
     const long tok = p.idx ? (long)p.idx[row] : (long)row;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -312,7 +320,7 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDe
   __shared__ __attribute__((aligned(1024))) unsigned char smem[smem_bytes<BM, BN, STAGES>()];
   const int m = p.m_dev ? *p.m_dev : p.m_max;
   if (m <= 0) return;
-  gemm_tile<BM, BN, WAVES_M, WAVES_N, STAGES>(p, m, smem);
+  gemm_tile<BM, BN, WAVES_M, WAVES_N, STAGES>(p, m, smem, threadIdx.x);
 }
 
 // ---- row count read on the device: the tile shape follows it -------------------------
@@ -327,9 +335,41 @@ __global__ void __launch_bounds__(256) gemm_bf16_rows_kernel(GemmDev p) {
   // for 52..256 rows at n = 4096 and n = 12288).  Beyond that, 128 x 128 tiles with a
   // two-stage ring, which fit the same 64 KiB.
   if (m <= 256)
-    gemm_tile<64, 64, 2, 2, 4>(p, m, smem);
+    gemm_tile<64, 64, 2, 2, 4>(p, m, smem, threadIdx.x);
   else
-    gemm_tile<128, 128, 2, 2, 2>(p, m, smem);
+    gemm_tile<128, 128, 2, 2, 2>(p, m, smem, threadIdx.x);
+}
+
+// The same for wide outputs (the three projections in one launch), 8 waves and 128 KiB
+// of LDS.  What bounds a projection of few rows is the rate at which one CU pulls
+// operand tiles out of L2 (measured 45-80 GB/s per CU whatever the ring depth), so the
+// shape that wins moves the fewest bytes per CU while still using every CU:
+//   256 x 192 (the all-row shape) once that fills the chip;
+//   128 x 128 (4 x 2 waves, 4 stages) once that gives at least kWideBigTiles tiles;
+//   else 64 x 64 tiles, one per workgroup while there are at most kWideSingle of them
+//   (the other four waves end at once; waves that have ended do not count at a
+//   barrier), and two per workgroup, one per team of four waves, beyond that.
+constexpr int kWideSmem = smem_bytes<128, 128, 4>();
+constexpr int kWideBigTiles = 160, kWideSingle = 256, kWideFullTiles = 200;
+__host__ __device__ inline int tiles_of(int m, int n, int bm, int bn) {
+  return ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
+}
+__global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kWideSmem];
+  static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 192, 2>() <= kWideSmem,
+                "shared buffer too small");
+  const int m = p.m_dev ? *p.m_dev : p.m_max;
+  if (m <= 0) return;
+  if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
+    gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x);
+  } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
+    gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x);
+  } else {
+    const int team = threadIdx.x >> 8;
+    const int teams = tiles_of(m, p.n, 64, 64) > kWideSingle ? 2 : 1;
+    if (team >= teams) return;
+    gemm_tile<64, 64, 2, 2, 4>(p, m, smem + team * smem_bytes<64, 64, 4>(), threadIdx.x & 255, team, teams);
+  }
 }
 
 GemmDev to_dev(const GemmArgs& g) {
@@ -381,6 +421,22 @@ hipError_t launch_rows(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
+hipError_t launch_rows_wide(const GemmArgs& g, hipStream_t s) {
+  // worst case over the row counts 1 .. m_max of the blocks any of the shapes needs;
+  // the 64 x 64 shape is only chosen below kWideBigTiles 128 x 128 tiles, each of which
+  // holds at most four small ones
+  const int small = tiles_of(g.m_max, g.n, 64, 64);
+  int pairs = (small + 1) / 2;
+  const int pairs_cap = (4 * (kWideBigTiles - 1) + 1) / 2;
+  if (pairs > pairs_cap) pairs = pairs_cap;
+  int blocks = small <= kWideSingle ? small : (pairs > kWideSingle ? pairs : kWideSingle);
+  const int big = tiles_of(g.m_max, g.n, 128, 128);
+  if (big >= kWideBigTiles && big > blocks) blocks = big;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(gemm_bf16_rows_wide_kernel, dim3(grid_for(blocks)), dim3(512), 0, s, to_dev(g));
+  return hipGetLastError();
+}
+
 }  // namespace
 
 // cfg: 0 = choose by shape; other values force one configuration (tuning aid).
@@ -400,9 +456,10 @@ hipError_t launch_gemm_bf16_cfg(const GemmArgs& g, int cfg, hipStream_t s) {
     case 13: return launch_fixed<128, 128, 4, 2, 4>(g, s);
     case 14: return launch_fixed<128, 256, 2, 4, 2>(g, s);
     case 20: return launch_rows(g, s);
+    case 21: return launch_rows_wide(g, s);
     default: break;
   }
-  if (g.m_dev) return launch_rows(g, s);
+  if (g.m_dev) return g.n >= 8192 ? launch_rows_wide(g, s) : launch_rows(g, s);
   // Row count known on the host.  Measured on MI355X (256 CUs): 256 x 256 tiles have
   // the least LDS-fill traffic per flop and win once they fill the chip; 256 x 192
   // gives exactly 256 tiles for 1024 x 12288; 128 x 128 with 8 waves is the best

@@ -81,6 +81,31 @@ def test_gemm_selected_rows_device_count(B, dtype, count):
         assert_close(got[rows], want[rows], dtype)
 
 
+@pytest.mark.parametrize("count", [0, 1, 52, 100, 205, 700, 1024])
+def test_gemm_selected_rows_wide_output(B, count):
+    """Wide outputs (n >= 8192) take the 8-wave kernel, whose tile shape follows the
+    device-side row count: one 64 x 64 tile per workgroup, two, 128 x 128, 256 x 192."""
+    r = _rng(count + 77)
+    n_tok, k, seg = 1024, 192, 4096
+    n = 3 * seg
+    a = store(r.standard_normal((n_tok, k)), "bf16")
+    w = store(r.standard_normal((k, n)) * 0.05, "bf16")
+    wt = B.dare_k_pack_weight(dev(w, "bf16"))
+    rows = np.sort(r.permutation(n_tok)[:count]).astype(np.int32)
+    idx = np.full(n_tok, 10 ** 6, dtype=np.int32)
+    idx[:count] = rows
+    outs = [torch.full((n_tok, seg), 3.0, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    m_dev = torch.tensor([count], dtype=torch.int32, device="cuda")
+    B.dare_k_gemm(dev(a, "bf16"), wt, outs, seg, idx=dev(idx), m_dev=m_dev, m_max=n_tok)
+    torch.cuda.synchronize()
+    got = np.concatenate([host(o) for o in outs], axis=1)
+    untouched = np.setdiff1d(np.arange(n_tok), rows)
+    assert np.all(got[untouched] == 3.0)
+    if count:
+        want = a[rows].astype(np.float64) @ w.astype(np.float64)
+        assert_close(got[rows], want, "bf16")
+
+
 def test_gemm_k_parts_feed_the_score(B):
     # the scored-columns projection cut along k: slabs of partial sums that the score
     # kernel adds up, against the uncut projection and the oracle's score
