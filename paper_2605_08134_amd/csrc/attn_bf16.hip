@@ -212,6 +212,7 @@ __device__ __forceinline__ void attn_block(const AttnDev& p, int b, int h, int q
         for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
     }
     const float neg_m = -m_run;
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
     float l_tile = 0.f;
     bf16x8 pf[PS];
 #pragma unroll
@@ -223,8 +224,8 @@ __device__ __forceinline__ void attn_block(const AttnDev& p, int b, int h, int q
         pr[1] = __builtin_amdgcn_exp2f(fmaf(acc_s[kt][r + 1], p.scale_log2, neg_m));
         const bf16x2 pb = __builtin_convertvector(pr, bf16x2);
         // the row sum is taken over the probabilities as rounded for the value product,
-        // so numerator and denominator carry the same rounding
-        l_tile += (float)pb[0] + (float)pb[1];
+        // so numerator and denominator carry the same rounding (v_dot2: += pb[0] + pb[1])
+        l_tile = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l_tile, false);
         pf[kt * 2 + (r >> 3)][r & 7] = pb[0];
         pf[kt * 2 + (r >> 3)][(r & 7) + 1] = pb[1];
       }
@@ -263,6 +264,8 @@ __device__ __forceinline__ void attn_block(const AttnDev& p, int b, int h, int q
   // ---- merge the key-waves (fixed order), normalise, store ----
   if (KW > 1) {
     constexpr int REGS = OT * 16 + 2;
+    static_assert((KW - 1) * QW * REGS * 64 * 4 <= attn_smem_bytes<DH, KW, TK, NST>(),
+                  "the merge area must fit into the stage memory");
     wait_all_and_barrier();  // all loads landed, all tiles consumed: stage memory is free
     float* xch = reinterpret_cast<float*>(smem);
     if (kw > 0) {
@@ -348,6 +351,7 @@ hipError_t launch_dh(const AttnDev& p, const AttnArgs& a, int cfg, hipStream_t s
     case 4: return launch_variant<DH, 1, 4, 32, 2>(p, a, s);
     case 5: return launch_variant<DH, 4, 2, 64, 2>(p, a, s);
     case 6: return launch_variant<DH, 2, 4, 32, 2>(p, a, s);
+    case 7: return launch_variant<DH, 4, 2, 32, 4>(p, a, s);
     default: break;
   }
   // measured on MI355X: 8 waves per block.  Full rows take the wide block (128 rows, 2
