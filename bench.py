@@ -98,6 +98,24 @@ def main():
         reuse = float(mask.float().mean().item())
         return ms, wall_ms / steps, reuse, int(sel_count.sum().item())
 
+    def latency_distribution(mode, xa, xb, steps):
+        """Per-step latency (an event after every step, outside the headline timing)."""
+        state = layer.new_state(Bn, T)
+        fill(state, xa)
+        run_steps(mode, xa, xb, state, 20)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        ev[0].record()
+        for i in range(steps):
+            x = xb if i % 2 == 0 else xa
+            layer.layer_step(mode, tau, x, state["q_prev"], state["k_cache"], state["v_cache"],
+                             state["o_cache"], state["o_cache"], mask, None, sel_count, None)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        us = np.sort(np.array([ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(steps)]))
+        return {"median": float(us[steps // 2]), "p10": float(us[steps // 10]),
+                "p90": float(us[(9 * steps) // 10])}
+
     pairs = {}
 
     def pair(fraction):
@@ -120,7 +138,7 @@ def main():
         for _ in range(n):
             B.dare_k_gemm(xb.view(Bn * T, d), wqkv_t, qkv_out, d, idx=idx, m_dev=m_dev, m_max=Bn * T)
 
-    dominant(10)
+    dominant(50)
     torch.cuda.synchronize()
     n_dom = 200
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -159,6 +177,11 @@ def main():
     ms_kvo, wall_kvo, reuse, n_ref = time_mode(B.MODE_KVO, xa, xb, args.steps, args.warmup)
     ms_dense, _, _, _ = time_mode(B.MODE_DENSE, xa, xb, max(20, args.steps // 4), args.warmup)
 
+    latency = None
+    if not args.quick:
+        latency = {"kvo_us": latency_distribution(B.MODE_KVO, xa, xb, 200),
+                   "dense_us": latency_distribution(B.MODE_DENSE, xa, xb, 100)}
+
     sweep = [{"mode": "kvo", "perturbed": 0.20, "reuse": reuse, "us": ms_kvo * 1e3,
               "tokens_per_s": Bn * T / (ms_kvo * 1e-3), "vs_dense": ms_kvo / ms_dense},
              {"mode": "dense", "perturbed": None, "reuse": 0.0, "us": ms_dense * 1e3,
@@ -192,6 +215,12 @@ def main():
         "bound": "mfma", "achieved": dg_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": dg_tflops / MFMA_BF16_PEAK_TFLOPS, "us_per_launch": dg_ms * 1e3}]
 
+    cold = peaks = None
+    if not args.quick:
+        cold = cold_weights(torch, B, layer, wdev, xa, xb, Bn, T, d, H, tau)
+        peaks = measured_peaks(torch, B, dev, d)
+        roofline_other += other_kernels_at_c2(torch, B, np, dev, d, H, Dh)
+
     # ---- CPU oracle on the host cores (reported baseline, not a target) ----------------------
     cpu = None
     if not args.no_cpu:
@@ -217,10 +246,156 @@ def main():
                    "latency_vs_dense": ms_kvo / ms_dense},
         "roofline": roofline,
         "roofline_other": roofline_other,
+        "measured_peaks": peaks,
+        "latency": latency,
+        "cold_weights": cold,
         "cpu_baseline": cpu,
         "sweep": sweep,
     }
     print(json.dumps(out))
+
+
+def _time_us(torch, fn, iters, warm=3):
+    fn(warm)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fn(iters)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters * 1e3
+
+
+def cold_weights(torch, B, layer0, wdev, xa, xb, Bn, T, d, H, tau, n_layers=8):
+    """The same step with weights that cannot stay in the 256 MB last-level cache:
+    round-robin over 8 layers with distinct weights (1 GiB of packed weights), each with
+    its own caches.  Weight values come from torch's seeded generator (timing only)."""
+    gen = torch.Generator(device=xa.device)
+    gen.manual_seed(4321)
+    layers, states = [layer0], []
+    for _ in range(n_layers - 1):
+        ws = [(torch.randn((d, d), device=xa.device, generator=gen) * 0.02).to(torch.bfloat16)
+              for _ in range(4)]
+        layers.append(B.DareLayer(*ws, n_heads=H, max_batch=Bn, max_seq=T))
+        del ws
+    mask = torch.zeros((Bn, T), dtype=torch.uint8, device=xa.device)
+    for ly in layers:
+        st = ly.new_state(Bn, T)
+        ly.layer_step(B.MODE_DENSE, 0.0, xa, st["q_prev"], st["k_cache"], st["v_cache"],
+                      st["o_cache"], st["o_cache"], mask)
+        states.append(st)
+    out = {}
+    for name, mode in (("kvo", B.MODE_KVO), ("dense", B.MODE_DENSE)):
+        def run(n, mode=mode):
+            # layer l sees x_cur, x_prev, x_cur, ... on its own consecutive steps
+            for i in range(n * n_layers):
+                ly, st = layers[i % n_layers], states[i % n_layers]
+                x = xb if (i // n_layers) % 2 == 0 else xa
+                ly.layer_step(mode, tau, x, st["q_prev"], st["k_cache"], st["v_cache"],
+                              st["o_cache"], st["o_cache"], mask)
+        out[name + "_us"] = _time_us(torch, run, 12, warm=2) / n_layers
+        out[name + "_reuse_last"] = float(mask.float().mean().item())
+    out["latency_vs_dense"] = out["kvo_us"] / out["dense_us"]
+    out["layers"] = n_layers
+    for ly in layers[1:]:
+        ly.destroy()
+    return out
+
+
+def measured_peaks(torch, B, dev, d):
+    """What this GPU sustains on a plain copy (1 GiB read + 1 GiB written) and on a
+    register-resident MFMA loop, next to the datasheet peaks the fractions use."""
+    src = torch.ones((1 << 17, d), dtype=torch.bfloat16, device=dev)   # 1 GiB
+    dst = torch.empty_like(src)
+    us = _time_us(torch, lambda n: [B.dare_k_copy_rows(src, dst) for _ in range(n)], 10)
+    copy_gbs = 2.0 * src.numel() * 2 / (us * 1e-6) / 1e9
+    del src, dst
+    res = {"hbm_copy_GBs": copy_gbs, "hbm_datasheet_GBs": HBM_PEAK_GBS,
+           "mfma_bf16_datasheet_TFLOPs": MFMA_BF16_PEAK_TFLOPS}
+    for pattern, key in ((0, "mfma_bf16_loop_zero_operands_TFLOPs"), (1, "mfma_bf16_loop_varied_operands_TFLOPs")):
+        flops = [0.0]
+
+        def run(n, pattern=pattern):
+            for _ in range(n):
+                flops[0] = B.dare_k_calib_mfma(2048, 4096, pattern)
+        us = _time_us(torch, run, 5, warm=2)
+        res[key] = flops[0] / (us * 1e-6) / 1e12
+    return res
+
+
+def other_kernels_at_c2(torch, B, np, dev, d, H, Dh):
+    """Kernel-level evidence at the large configuration (8 x 2048 tokens): the stages that
+    move too few bytes at 1024 tokens to say anything about bandwidth, and the
+    MFMA-bound stages at a size that fills the chip."""
+    Bn, T = 8, 2048
+    n_tok = Bn * T
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    rnd = lambda *shape: torch.randn(shape, device=dev, generator=gen)
+    out = []
+    # drift score + decision + score-cache update
+    q_new = rnd(n_tok, Dh)
+    q_prev = rnd(n_tok, Dh)
+    scores = torch.empty(n_tok, dtype=torch.float32, device=dev)
+    mask = torch.empty(n_tok, dtype=torch.uint8, device=dev)
+    us = _time_us(torch, lambda n: [B.dare_k_score(q_new, q_prev, 5e-3, False, scores, mask)
+                                    for _ in range(n)], 50)
+    nbytes = n_tok * (3 * Dh * 4 + 5)
+    out.append({"kernel": "score_kernel (%d tokens)" % n_tok, "bound": "hbm",
+                "achieved": nbytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "us_per_launch": us})
+    # compaction
+    mask.copy_((torch.rand(n_tok, device=dev, generator=gen) < 0.8).to(torch.uint8))
+    sel_idx = torch.empty(n_tok, dtype=torch.int32, device=dev)
+    sel_count = torch.empty(Bn, dtype=torch.int32, device=dev)
+    sel_off = torch.empty(Bn + 1, dtype=torch.int32, device=dev)
+    us = _time_us(torch, lambda n: [B.dare_k_compact(mask, Bn, T, sel_idx, sel_count, sel_off)
+                                    for _ in range(n)], 50)
+    n_sel = int(sel_off[-1].item())
+    nbytes = n_tok + 4 * n_sel
+    out.append({"kernel": "compact_kernel (%d tokens, %d refreshed)" % (n_tok, n_sel), "bound": "hbm",
+                "achieved": nbytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "us_per_launch": us,
+                "note": "latency bound: one pass over %d KiB" % (nbytes >> 10)})
+    # row copy of the refreshed rows (cache merge when out and o_cache differ)
+    src = rnd(n_tok, d).to(torch.bfloat16)
+    dst = torch.empty_like(src)
+    m_dev = sel_off[-1:].clone()
+    us = _time_us(torch, lambda n: [B.dare_k_copy_rows(src, dst, idx=sel_idx, m_dev=m_dev)
+                                    for _ in range(n)], 50)
+    nbytes = 2 * n_sel * d * 2
+    out.append({"kernel": "copy_rows_kernel (%d rows of 8 KiB)" % n_sel, "bound": "hbm",
+                "achieved": nbytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "us_per_launch": us})
+    # refreshed-row Q/K/V projection at this size: MFMA bound (n well above the crossover)
+    wt = (rnd(3 * d, d) * 0.02).to(torch.bfloat16)
+    outs = [torch.empty((n_tok, d), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+    us = _time_us(torch, lambda n: [B.dare_k_gemm(src, wt, outs, d, idx=sel_idx, m_dev=m_dev, m_max=n_tok)
+                                    for _ in range(n)], 10)
+    tf = 2.0 * n_sel * d * 3 * d / (us * 1e-6) / 1e12
+    out.append({"kernel": "gemm_bf16_rows_wide_kernel (%d refreshed rows x %d x %d)" % (n_sel, 3 * d, d),
+                "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "us_per_launch": us})
+    us = _time_us(torch, lambda n: [B.dare_k_gemm(src, wt, outs, d) for _ in range(n)], 5)
+    tf = 2.0 * n_tok * d * 3 * d / (us * 1e-6) / 1e12
+    out.append({"kernel": "gemm_bf16_kernel (all-row Q/K/V projection, %d x %d x %d)" % (n_tok, 3 * d, d),
+                "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "us_per_launch": us})
+    # attention, all rows and refreshed rows
+    q, k, v = outs
+    att = torch.empty_like(q)
+    us = _time_us(torch, lambda n: [B.dare_k_attention(q, k, v, att, Bn, T, H, Dh) for _ in range(n)], 5)
+    tf = 4.0 * n_tok * T * d / (us * 1e-6) / 1e12
+    out.append({"kernel": "attn_bf16_kernel (all rows, %d x %d tokens)" % (Bn, T), "bound": "mfma",
+                "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "us_per_launch": us})
+    us = _time_us(torch, lambda n: [B.dare_k_attention(q, k, v, att, Bn, T, H, Dh, idx=sel_idx, sel_off=sel_off)
+                                    for _ in range(n)], 10)
+    tf = 4.0 * n_sel * T * d / (us * 1e-6) / 1e12
+    out.append({"kernel": "attn_bf16_kernel (%d refreshed rows of %d x %d tokens)" % (n_sel, Bn, T),
+                "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "us_per_launch": us})
+    return out
 
 
 def stored_traffic():

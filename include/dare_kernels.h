@@ -106,6 +106,18 @@ dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows,
                              int row_bytes, const int32_t* idx,
                              const int32_t* m_dev, void* hip_stream);
 
+/*
+ * Calibration of the matrix-core peak that the projection and attention kernels are
+ * measured against (no paper passage: measurement aid).  Enqueues n_blocks workgroups
+ * of 4 waves, each wave issuing n_iter * 8 v_mfma_f32_32x32x16_bf16 on registers only.
+ * pattern 0: zero operands; 1: operands that differ per lane.  *flops (HOST pointer,
+ * may be NULL) receives the flop count of the launch; out (device, may be NULL) is
+ * never written in practice.  Time the launch with events: flops / time is what the
+ * matrix pipes sustain.
+ */
+dare_status dare_k_calib_mfma(int n_blocks, int n_iter, int pattern, float* out,
+                              double* flops, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ MODE_NAMES = {MODE_DENSE: "dense", MODE_KV: "kv", MODE_O: "o", MODE_KVO: "kvo"}
 EXPORTS = (
     "dare_create", "dare_layer_step", "dare_destroy", "dare_last_error", "dare_version",
     "dare_k_pack_weight", "dare_k_gemm", "dare_k_score", "dare_k_compact",
-    "dare_k_attention", "dare_k_copy_rows",
+    "dare_k_attention", "dare_k_copy_rows", "dare_k_calib_mfma",
 )
 
 
@@ -80,6 +80,8 @@ def lib():
     L.dare_k_attention.restype = i32
     L.dare_k_copy_rows.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     L.dare_k_copy_rows.restype = i32
+    L.dare_k_calib_mfma.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.dare_k_calib_mfma.restype = i32
     _lib = L
     return L
 
@@ -217,3 +219,10 @@ def dare_k_copy_rows(src, dst, idx=None, m_dev=None, stream=None):
     row_bytes = src.shape[-1] * src.element_size()
     _check(lib().dare_k_copy_rows(_ptr(src), _ptr(dst), n_rows, row_bytes, _ptr(idx), _ptr(m_dev),
                                   _stream(stream)))
+
+
+def dare_k_calib_mfma(n_blocks, n_iter, pattern, stream=None):
+    """Enqueue the register-resident MFMA loop; returns the flop count of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().dare_k_calib_mfma(n_blocks, n_iter, pattern, None, ctypes.byref(flops), _stream(stream)))
+    return flops.value

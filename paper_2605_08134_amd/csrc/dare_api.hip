@@ -417,4 +417,11 @@ dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows, int row_byt
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }
 
+dare_status dare_k_calib_mfma(int n_blocks, int n_iter, int pattern, float* out, double* flops,
+                              void* hip_stream) {
+  if (n_blocks < 0 || n_iter < 0 || (pattern != 0 && pattern != 1)) return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_mfma_loop(n_blocks, n_iter, pattern, out, flops, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
 }  // extern "C"

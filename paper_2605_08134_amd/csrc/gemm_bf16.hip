@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_rows_kernel(GemmDev p) {
 // of LDS.  What bounds a projection of few rows is the rate at which one CU pulls
 // operand tiles out of L2 (measured 45-80 GB/s per CU whatever the ring depth), so the
 // shape that wins moves the fewest bytes per CU while still using every CU:
-//   256 x 192 (the all-row shape) once that fills the chip;
+//   256 x 256 and 256 x 192 (the all-row shapes) once they fill the chip;
 //   128 x 128 (4 x 2 waves, 4 stages) once that gives at least kWideBigTiles tiles;
 //   else 64 x 64 tiles, one per workgroup while there are at most kWideSingle of them
 //   (the other four waves end at once; waves that have ended do not count at a
@@ -356,11 +356,13 @@ __host__ __device__ inline int tiles_of(int m, int n, int bm, int bn) {
 }
 __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kWideSmem];
-  static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 192, 2>() <= kWideSmem,
+  static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem,
                 "shared buffer too small");
   const int m = p.m_dev ? *p.m_dev : p.m_max;
   if (m <= 0) return;
-  if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
+  if (p.n % 256 == 0 && tiles_of(m, p.n, 256, 256) >= 2 * kWideSingle) {
+    gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x);
+  } else if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
     gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x);
   } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
     gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x);

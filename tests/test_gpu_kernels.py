@@ -81,12 +81,14 @@ def test_gemm_selected_rows_device_count(B, dtype, count):
         assert_close(got[rows], want[rows], dtype)
 
 
-@pytest.mark.parametrize("count", [0, 1, 52, 100, 205, 700, 1024])
-def test_gemm_selected_rows_wide_output(B, count):
+@pytest.mark.parametrize("n_tok,count", [(1024, 0), (1024, 1), (1024, 52), (1024, 100), (1024, 205),
+                                         (1024, 700), (1024, 1024), (3072, 2900)])
+def test_gemm_selected_rows_wide_output(B, n_tok, count):
     """Wide outputs (n >= 8192) take the 8-wave kernel, whose tile shape follows the
-    device-side row count: one 64 x 64 tile per workgroup, two, 128 x 128, 256 x 192."""
+    device-side row count: one 64 x 64 tile per workgroup, two, 128 x 128, 256 x 192,
+    256 x 256."""
     r = _rng(count + 77)
-    n_tok, k, seg = 1024, 192, 4096
+    k, seg = 192, 4096
     n = 3 * seg
     a = store(r.standard_normal((n_tok, k)), "bf16")
     w = store(r.standard_normal((k, n)) * 0.05, "bf16")
