@@ -155,7 +155,7 @@ def main():
     dom_bytes = 3 * d * d * 2 + n_sel * d * 2 + 3 * n_sel * d * 2
     dom_flops = 2.0 * n_sel * d * 3 * d
     roofline = {
-        "kernel": "gemm_bf16_kernel (refreshed-row Q/K/V projection, %d rows x %d x %d)" % (n_sel, 3 * d, d),
+        "kernel": "gemm_bf16_rows_wide_kernel (refreshed-row Q/K/V projection, %d rows x %d x %d)" % (n_sel, 3 * d, d),
         "bound": "hbm",
         "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9,
         "peak": HBM_PEAK_GBS,
@@ -410,7 +410,7 @@ def stored_traffic():
     path = os.path.join(ROOT, "profiles", "gemm_rows_qkv_llada8b_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
+            if line.strip().startswith("traffic_bytes_per_launch"):
                 return float(line.split("=")[1].split()[0])
     except OSError:
         pass
