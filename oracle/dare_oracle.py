@@ -40,6 +40,18 @@ Readings taken where the paper is silent or has two forms:
   * a dense or DARE-O step writes the dense K, V into the K/V caches, so a later
     DARE-KV step starts from valid rows
   * index lists are ascending flat token ids b*T + i.
+  * the block around the layer (``block_step``).  Alg. 1/2 line 1 normalises the
+    hidden state before the projections: ``layer_norm`` is that line; ``rms_norm`` is
+    the variant LLaDA-class models use in its place.  The paper says nothing about
+    position encoding or the residual connection; for a model that has them the
+    reading is: rotary embedding (pairs of neighbouring channels (2i, 2i+1) of each
+    head, angle = position * base^(-2i/head_dim)) on the queries and on the keys as
+    they are projected, so the K cache holds rotated keys and a reused row keeps the
+    rotation of its own position; the drift score is taken on the query BEFORE the
+    rotation (the rotation of a token is the same at both steps, so the cosine is
+    the same up to rounding); the output cache holds the attention block's output
+    before the residual sum, and ``out = x + O`` is formed for every row from the
+    current hidden state.
   * precision.  The paper runs in BF16 (Sec. 5, App. A): the tensors its
     algorithms name -- Q, K, V, the attention rows before Wo, the layer output --
     are bf16 tensors, with wide accumulation inside each product.  ``storage=None``
@@ -154,12 +166,49 @@ def dense_layer(x, wq, wk, wv, wo, n_heads):
     return out, Q, K, V
 
 
+def layer_norm(x, gain, bias=None, eps=1e-5):
+    """Alg. 1/2 line 1: per token, (x - mean) / sqrt(var + eps) * gain + bias over the
+    channel axis (biased variance)."""
+    x = _f64(x)
+    mu = np.mean(x, axis=-1, keepdims=True)
+    var = np.mean((x - mu) ** 2, axis=-1, keepdims=True)
+    y = (x - mu) / np.sqrt(var + eps) * _f64(gain)
+    return y if bias is None else y + _f64(bias)
+
+
+def rms_norm(x, gain, eps=1e-5):
+    """The root-mean-square variant of line 1: x / sqrt(mean(x^2) + eps) * gain."""
+    x = _f64(x)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * _f64(gain)
+
+
+def rope(x, positions, n_heads, base=10000.0):
+    """Rotary position embedding of x [..., T, d] with per-token positions [T]: in
+    every head, the channel pair (2i, 2i+1) is rotated by positions * base^(-2i/Dh)."""
+    x = _f64(x)
+    d = x.shape[-1]
+    dh = d // n_heads
+    i = np.arange(dh // 2, dtype=np.float64)
+    theta = base ** (-2.0 * i / dh)                              # [Dh/2]
+    ang = _f64(positions)[:, None] * theta[None, :]              # [T, Dh/2]
+    c = np.tile(np.cos(ang), (1, n_heads))                       # [T, d/2], head after head
+    s = np.tile(np.sin(ang), (1, n_heads))
+    xe, xo = x[..., 0::2], x[..., 1::2]
+    y = np.empty_like(x)
+    y[..., 0::2] = xe * c - xo * s
+    y[..., 1::2] = xe * s + xo * c
+    return y
+
+
 def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
-               n_heads, score_head=0, storage=None):
+               n_heads, score_head=0, storage=None, rope_base=None):
     """One step of the layer in mode DENSE / KV (Alg. 1) / O (Alg. 2) / KVO.
 
     x [B,T,d]; w* [d,d]; q_prev [B,T,Dh] (or [B,T,d] when score_head = -1);
     k_cache, v_cache, o_cache [B,T,d] hold the previous step's state.
+    rope_base: None, or the base of the rotary embedding applied to Q and to the K rows
+    projected at this step (see the header).
     Returns a dict with out, k_cache, v_cache, o_cache, q_prev (all updated,
     float64), scores [B,T] float64, reuse_mask uint8 [B,T] (1 = reused),
     sel_idx, sel_count, sel_off, and exact = {out, k_cache, v_cache} before the
@@ -185,7 +234,12 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
     else:
         reuse = reuse_decision(scores, tau)
     sel_idx, sel_count, sel_off = selection(reuse)
-    Qs = round_storage(Q, storage)
+    # rotary embedding of queries and of the keys projected at this step (position =
+    # index in the sequence); the score above used the unrotated query
+    pos = np.arange(T, dtype=np.float64)
+    rot = (lambda a, rows=None: a) if rope_base is None else (
+        lambda a, rows=None: rope(a, pos if rows is None else pos[rows], n_heads, rope_base))
+    Qs = round_storage(rot(Q), storage)
 
     # Keys and values.
     if mode in (MODE_KV, MODE_KVO):
@@ -194,11 +248,11 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
         V_exact = _f64(v_cache).copy()
         for b in range(B):
             rows = np.flatnonzero(~reuse[b])
-            K_exact[b, rows] = x[b, rows] @ wk
+            K_exact[b, rows] = rot(x[b, rows] @ wk, rows)
             V_exact[b, rows] = x[b, rows] @ wv
     else:
         # Alg. 2 line 7 / App. E.2.
-        K_exact = x @ wk
+        K_exact = rot(x @ wk)
         V_exact = x @ wv
     K = round_storage(K_exact, storage)
     V = round_storage(V_exact, storage)
@@ -232,6 +286,34 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
         "sel_count": sel_count,
         "sel_off": sel_off,
     }
+
+
+def block_step(mode, tau, x, norm, gain, bias, eps, wq, wk, wv, wo, q_prev, k_cache,
+               v_cache, o_cache, n_heads, score_head=0, storage=None, rope_base=None,
+               residual=True):
+    """The attention block around ``layer_step``: h = norm(x) (Alg. 1/2 line 1; norm is
+    "layer", "rms" or None), the layer step on h, then out = x + O when residual.
+
+    o_cache holds O, the block output before the residual sum.  Returns layer_step's
+    dict (its "out" and "o_cache" are O) plus "h" and "block_out"; exact["block_out"]
+    is x + exact O."""
+    x = _f64(x)
+    if norm == "layer":
+        h = layer_norm(x, gain, bias, eps)
+    elif norm == "rms":
+        h = rms_norm(x, gain, eps)
+    elif norm is None:
+        h = x
+    else:
+        raise ValueError("norm must be 'layer', 'rms' or None")
+    h = round_storage(h, storage)          # the normalised hidden state is a stored tensor
+    r = layer_step(mode, tau, h, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
+                   n_heads, score_head=score_head, storage=storage, rope_base=rope_base)
+    r["h"] = h
+    exact_block = x + r["out"] if residual else r["out"].copy()
+    r["exact"]["block_out"] = exact_block
+    r["block_out"] = round_storage(exact_block, storage)
+    return r
 
 
 def step_o_prewo(tau, x, wq, wk, wv, wo, q_prev, attn_cache, n_heads,
