@@ -114,6 +114,56 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
                             void* out, uint8_t* reuse_mask, int32_t* sel_idx,
                             int32_t* sel_count, float* scores, void* hip_stream);
 
+/*
+ * The attention block around the layer step: the normalisation of the hidden state
+ * that both algorithms start with (Alg. 1/2 line 1), rotary position embedding of the
+ * projected queries and keys, and the residual sum.  The paper states only line 1;
+ * position encoding and residual are what a model built from such layers needs, read
+ * as follows: the drift score is taken on the query before the rotation; keys are
+ * rotated as they are projected, so the K cache holds rotated keys and a reused row
+ * keeps the rotation of its own position; the output cache holds the block output
+ * before the residual sum, which is formed for every row from the current x.
+ */
+enum { DARE_NORM_NONE = 0, DARE_NORM_LAYER = 1, DARE_NORM_RMS = 2 };
+
+typedef struct {
+  uint32_t struct_size; /* = sizeof(dare_block_config)                              */
+  int32_t norm;         /* DARE_NORM_LAYER: (x - mean) / sqrt(var + eps) * gain + bias
+                           (Alg. 1/2 line 1); DARE_NORM_RMS: x / sqrt(mean(x^2) + eps)
+                           * gain; DARE_NORM_NONE: the hidden state is used as it is  */
+  float eps;
+  float rope_base;      /* 0: no rotary embedding.  Else the channel pair (2i, 2i+1)
+                           of every head of Q and K is rotated by
+                           position * rope_base^(-2i / head_dim), position = index of
+                           the token in its sequence                                */
+  int32_t residual;     /* 1: out = x + O; 0: out = O                               */
+} dare_block_config;
+
+/*
+ * Attach a block configuration to a context (replaces an earlier one).  gain, bias:
+ * device pointers to [hidden] vectors of the context's dtype (gain required unless
+ * norm is NONE; bias optional, LayerNorm only); they are copied.  Builds the rotary
+ * table for max_seq positions on the host in double precision and uploads it.
+ * Synchronises the stream.  Errors: INVALID_ARG, OOM, HIP.
+ */
+dare_status dare_block_attach(dare_ctx* ctx, const dare_block_config* cfg,
+                              const void* gain, const void* bias, void* hip_stream);
+
+/*
+ * One step of the attached block: h = norm(x); the layer step of dare_layer_step on h
+ * with the rotary embedding applied to Q and to the K rows projected at this step;
+ * out = x + O (residual = 1) or O.  Arguments as dare_layer_step, except:
+ *   x        in      [batch, seq, hidden] dtype: the hidden state BEFORE normalisation
+ *   o_cache  in/out  the block output O before the residual sum
+ *   out      out     with residual = 1 it must not be o_cache (INVALID_ARG)
+ * Errors: as dare_layer_step; INVALID_ARG when no block is attached.
+ */
+dare_status dare_block_step(dare_ctx* ctx, int mode, float threshold, int batch,
+                            int seq, const void* x, float* q_prev, void* k_cache,
+                            void* v_cache, void* o_cache, void* out,
+                            uint8_t* reuse_mask, int32_t* sel_idx, int32_t* sel_count,
+                            float* scores, void* hip_stream);
+
 /* Free a context and its device memory.  NULL is a no-op. */
 dare_status dare_destroy(dare_ctx* ctx);
 

@@ -107,6 +107,40 @@ dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows,
                              const int32_t* m_dev, void* hip_stream);
 
 /*
+ * The projection above with the rotary embedding in its epilogue (see dare_block_config
+ * in dare.h): output columns [0, rope_cols) are rotated, channel pair (2i, 2i+1) of
+ * every head_dim-wide head by the angle whose (cos, sin) is
+ * rope_table[(t % seq) * head_dim/2 + i], t the token id of the row; the fp32 copy c32
+ * keeps the unrotated values.  rope_table: fp32 [positions, head_dim/2, 2].  rope_cols
+ * is a multiple of head_dim; seg_n a multiple of head_dim.  No k_parts.
+ */
+dare_status dare_k_gemm_rope(int dtype, const void* a, int lda, const void* wt, int n,
+                             int k, int m_max, const int32_t* idx,
+                             const int32_t* m_dev, void* const* c, int ldc, int seg_n,
+                             float* c32, int c32_cols, const float* rope_table,
+                             int rope_cols, int head_dim, int seq, void* hip_stream);
+
+/*
+ * Rotary table for positions 0 .. n_pos-1: table[p, i] = (cos, sin) of
+ * p * base^(-2i / head_dim), computed on the HOST in double precision and copied to
+ * the device pointer `table` (fp32 [n_pos, head_dim/2, 2]) with a synchronous copy.
+ */
+dare_status dare_k_rope_table(float* table, int n_pos, int head_dim, double base);
+
+/*
+ * Normalisation of token rows (Alg. 1/2 line 1): kind DARE_NORM_LAYER or
+ * DARE_NORM_RMS, formulas as in dare_block_config.  x, out [n_rows, d] dtype (out may
+ * be x), gain [d], bias [d] or NULL; d a multiple of 8; fp32 statistics.
+ */
+dare_status dare_k_norm(int dtype, int kind, const void* x, const void* gain,
+                        const void* bias, float eps, int n_rows, int d, void* out,
+                        void* hip_stream);
+
+/* Residual sum out = x + o over n_elems elements (a multiple of 8) of dtype. */
+dare_status dare_k_residual_add(int dtype, const void* x, const void* o, void* out,
+                                long n_elems, void* hip_stream);
+
+/*
  * Calibration of the matrix-core peak that the projection and attention kernels are
  * measured against (no paper passage: measurement aid).  Enqueues n_blocks workgroups
  * of 4 waves, each wave issuing n_iter * 8 v_mfma_f32_32x32x16_bf16 on registers only.

@@ -21,7 +21,11 @@ EXPORTS = (
     "dare_create", "dare_layer_step", "dare_destroy", "dare_last_error", "dare_version",
     "dare_k_pack_weight", "dare_k_gemm", "dare_k_score", "dare_k_compact",
     "dare_k_attention", "dare_k_copy_rows", "dare_k_calib_mfma",
+    "dare_block_attach", "dare_block_step", "dare_k_gemm_rope", "dare_k_rope_table",
+    "dare_k_norm", "dare_k_residual_add",
 )
+NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2
+NORM_KINDS = {None: NORM_NONE, "layer": NORM_LAYER, "rms": NORM_RMS}
 
 
 class DareConfig(ctypes.Structure):
@@ -36,6 +40,16 @@ class DareConfig(ctypes.Structure):
         ("score_head", ctypes.c_int32),
         ("device", ctypes.c_int32),
         ("flags", ctypes.c_uint32),
+    ]
+
+
+class DareBlockConfig(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("norm", ctypes.c_int32),
+        ("eps", ctypes.c_float),
+        ("rope_base", ctypes.c_float),
+        ("residual", ctypes.c_int32),
     ]
 
 
@@ -82,6 +96,19 @@ def lib():
     L.dare_k_copy_rows.restype = i32
     L.dare_k_calib_mfma.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.dare_k_calib_mfma.restype = i32
+    L.dare_block_attach.argtypes = [vp, ctypes.POINTER(DareBlockConfig), vp, vp, vp]
+    L.dare_block_attach.restype = i32
+    L.dare_block_step.argtypes = [vp, i32, f32, i32, i32] + [vp] * 11
+    L.dare_block_step.restype = i32
+    L.dare_k_gemm_rope.argtypes = [i32, vp, i32, vp, i32, i32, i32, vp, vp, ctypes.POINTER(vp), i32, i32,
+                                   vp, i32, vp, i32, i32, i32, vp]
+    L.dare_k_gemm_rope.restype = i32
+    L.dare_k_rope_table.argtypes = [vp, i32, i32, ctypes.c_double]
+    L.dare_k_rope_table.restype = i32
+    L.dare_k_norm.argtypes = [i32, i32, vp, vp, vp, f32, i32, i32, vp, vp]
+    L.dare_k_norm.restype = i32
+    L.dare_k_residual_add.argtypes = [i32, vp, vp, vp, ctypes.c_long, vp]
+    L.dare_k_residual_add.restype = i32
     _lib = L
     return L
 
@@ -157,6 +184,23 @@ class DareLayer:
                                    _stream(stream))
         _check(st, self._ctx)
 
+    def block_attach(self, norm=None, gain=None, bias=None, eps=1e-5, rope_base=0.0, residual=True,
+                     stream=None):
+        """dare_block_attach: norm is None, "layer" or "rms"."""
+        cfg = DareBlockConfig(ctypes.sizeof(DareBlockConfig), NORM_KINDS[norm], eps, rope_base,
+                              int(bool(residual)))
+        st = lib().dare_block_attach(self._ctx, ctypes.byref(cfg), _ptr(gain), _ptr(bias), _stream(stream))
+        _check(st, self._ctx)
+
+    def block_step(self, mode, threshold, x, q_prev, k_cache, v_cache, o_cache, out,
+                   reuse_mask, sel_idx=None, sel_count=None, scores=None, stream=None):
+        batch, seq, _ = x.shape
+        st = lib().dare_block_step(self._ctx, mode, threshold, batch, seq, _ptr(x), _ptr(q_prev),
+                                   _ptr(k_cache), _ptr(v_cache), _ptr(o_cache), _ptr(out),
+                                   _ptr(reuse_mask), _ptr(sel_idx), _ptr(sel_count), _ptr(scores),
+                                   _stream(stream))
+        _check(st, self._ctx)
+
     def destroy(self):
         if self._ctx:
             lib().dare_destroy(self._ctx)
@@ -191,6 +235,42 @@ def dare_k_gemm(a, wt, outs, seg_n, idx=None, m_dev=None, m_max=None, c32=None, 
     _check(lib().dare_k_gemm(dtype, _ptr(a), a.shape[-1], _ptr(wt), n, k, m_max, _ptr(idx), _ptr(m_dev),
                              arr, ldc, seg_n, _ptr(c32), 0 if c32 is None else c32.shape[-1],
                              k_parts, 0 if c32 is None else m_max * c32.shape[-1], _stream(stream)))
+
+
+def dare_k_gemm_rope(a, wt, outs, seg_n, rope_table, rope_cols, head_dim, seq, idx=None, m_dev=None,
+                     m_max=None, c32=None, stream=None):
+    import torch
+    n, k = wt.shape
+    dtype = DARE_BF16 if a.dtype == torch.bfloat16 else DARE_F32
+    arr = (ctypes.c_void_p * 3)(*[_ptr(o) for o in list(outs) + [None] * (3 - len(outs))])
+    ldc = next(o for o in outs if o is not None).shape[-1]
+    if m_max is None:
+        m_max = a.shape[0] if idx is None else idx.shape[0]
+    _check(lib().dare_k_gemm_rope(dtype, _ptr(a), a.shape[-1], _ptr(wt), n, k, m_max, _ptr(idx),
+                                  _ptr(m_dev), arr, ldc, seg_n, _ptr(c32),
+                                  0 if c32 is None else c32.shape[-1], _ptr(rope_table), rope_cols,
+                                  head_dim, seq, _stream(stream)))
+
+
+def dare_k_rope_table(n_pos, head_dim, base, device="cuda"):
+    import torch
+    table = torch.empty((n_pos, head_dim // 2, 2), dtype=torch.float32, device=device)
+    _check(lib().dare_k_rope_table(_ptr(table), n_pos, head_dim, float(base)))
+    return table
+
+
+def dare_k_norm(kind, x, gain, bias, eps, out, stream=None):
+    import torch
+    dtype = DARE_BF16 if x.dtype == torch.bfloat16 else DARE_F32
+    d = x.shape[-1]
+    _check(lib().dare_k_norm(dtype, NORM_KINDS[kind], _ptr(x), _ptr(gain), _ptr(bias), eps,
+                             x.numel() // d, d, _ptr(out), _stream(stream)))
+
+
+def dare_k_residual_add(x, o, out, stream=None):
+    import torch
+    dtype = DARE_BF16 if x.dtype == torch.bfloat16 else DARE_F32
+    _check(lib().dare_k_residual_add(dtype, _ptr(x), _ptr(o), _ptr(out), x.numel(), _stream(stream)))
 
 
 def dare_k_score(q_new, q_prev, threshold, force_refresh, scores, mask, n_parts=1, stream=None):

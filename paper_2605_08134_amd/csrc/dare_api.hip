@@ -26,7 +26,20 @@ struct dare_ctx {
   int32_t* sel_off;    // [max_batch + 1]
   void* attn_work;
   uint64_t attn_work_bytes;
+  // the block around the layer (dare_block_attach)
+  bool has_block, has_bias;
+  dare_block_config block;
+  void* gain;          // [d] copies of the caller's vectors
+  void* bias;          // [d] or nullptr
+  void* h_buf;         // [max tokens, d] normalised hidden state
+  float* rope_table;   // [max_seq, head_dim / 2, 2] (cos, sin), or nullptr
   std::string err;
+};
+
+// what the block adds to a layer step (all null / zero for dare_layer_step)
+struct BlockExtras {
+  const float* rope;   // rotary table or nullptr
+  const void* x_resid; // hidden state before normalisation when out = x + O, else nullptr
 };
 
 namespace {
@@ -64,7 +77,7 @@ struct DeviceGuard {
 void free_ctx(dare_ctx* c) {
   if (!c) return;
   void* bufs[] = {c->wqkv_t, c->wo_t, c->q_buf, c->attn_buf, c->q_new, c->sel_idx, c->sel_off,
-                  c->attn_work};
+                  c->attn_work, c->gain, c->bias, c->h_buf, c->rope_table};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   delete c;
@@ -122,6 +135,9 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, 
   c->wqkv_t = c->wo_t = c->q_buf = c->attn_buf = c->attn_work = nullptr;
   c->q_new = nullptr;
   c->sel_idx = c->sel_off = nullptr;
+  c->has_block = c->has_bias = false;
+  c->gain = c->bias = c->h_buf = nullptr;
+  c->rope_table = nullptr;
   const size_t d = cfg->hidden;
   c->attn_work_bytes = cfg->dtype == DARE_BF16
                            ? attn_bf16_work_bytes(cfg->max_batch, cfg->max_seq, cfg->n_heads, cfg->head_dim)
@@ -174,11 +190,11 @@ dare_status dare_destroy(dare_ctx* ctx) {
   return DARE_OK;
 }
 
-dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch, int seq,
-                            const void* hidden, float* q_prev, void* k_cache, void* v_cache,
-                            void* o_cache, void* out, uint8_t* reuse_mask, int32_t* sel_idx,
-                            int32_t* sel_count, float* scores, void* hip_stream) {
-  if (!ctx) return DARE_ERR_INVALID_ARG;
+namespace {
+
+dare_status check_step_args(dare_ctx* ctx, int mode, float threshold, int batch, int seq, const void* hidden,
+                            const float* q_prev, const void* k_cache, const void* v_cache,
+                            const void* o_cache, const void* out, const uint8_t* reuse_mask) {
   if (mode != DARE_MODE_DENSE && mode != DARE_MODE_KV && mode != DARE_MODE_O && mode != DARE_MODE_KVO)
     return fail(ctx, DARE_ERR_INVALID_ARG, "unknown mode");
   if (!hidden || !q_prev || !k_cache || !v_cache || !o_cache || !out || !reuse_mask)
@@ -187,7 +203,15 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
   if (batch > ctx->cfg.max_batch || seq > ctx->cfg.max_seq)
     return fail(ctx, DARE_ERR_INVALID_ARG, "batch or seq exceeds the context's maximum");
   if (std::isnan(threshold)) return fail(ctx, DARE_ERR_INVALID_ARG, "threshold is NaN");
+  return DARE_OK;
+}
 
+// The launches of one layer step on already-normalised hidden states (arguments checked
+// by the caller).
+dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int seq, const void* hidden,
+                      float* q_prev, void* k_cache, void* v_cache, void* o_cache, void* out,
+                      uint8_t* reuse_mask, int32_t* sel_idx, int32_t* sel_count, float* scores,
+                      const BlockExtras& bx, void* hip_stream) {
   const dare_config& cf = ctx->cfg;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int d = cf.hidden, n_tok = batch * seq, sw = ctx->score_width;
@@ -212,15 +236,21 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
   g.c32 = ctx->q_new;
   g.c32_cols = sw;
   g.wt = wq_t;
+  g.rope = bx.rope;  // queries and keys are rotated as they are written; the fp32 copy
+  g.rope_dh = cf.head_dim;  // that feeds the score is not
+  g.rope_seq = seq;
   if (mode == DARE_MODE_DENSE || mode == DARE_MODE_O) {
     g.n = 3 * d;  // Q, K, V for every row (App. E.2; Alg. 2 lines 2 and 7)
     g.c[0] = ctx->q_buf;
     g.c[1] = k_cache;
     g.c[2] = v_cache;
+    g.rope_cols = 2 * d;
   } else if (mode == DARE_MODE_KV) {
     g.n = d;  // Q for every row (Alg. 1 line 2)
     g.c[0] = ctx->q_buf;
+    g.rope_cols = d;
   } else {
+    g.rope = nullptr;
     g.n = sw;  // only the scored columns of Q for every row
     // few output tiles, long k: cut k into ranges that the score kernel adds up
     if (cf.dtype == DARE_BF16) {
@@ -259,17 +289,22 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
     r.m_dev = n_sel;
     r.ldc = d;
     r.seg_n = d;
+    r.rope = bx.rope;
+    r.rope_dh = cf.head_dim;
+    r.rope_seq = seq;
     if (mode == DARE_MODE_KV) {
       r.wt = wkv_t;
       r.n = 2 * d;
       r.c[0] = k_cache;
       r.c[1] = v_cache;
+      r.rope_cols = d;
     } else {
       r.wt = wq_t;
       r.n = 3 * d;
       r.c[0] = ctx->q_buf;
       r.c[1] = k_cache;
       r.c[2] = v_cache;
+      r.rope_cols = 2 * d;
     }
     if ((e = gemm(ctx, r, s)) != hipSuccess) return fail_hip(ctx, e, "refreshed-row projection");
   }
@@ -305,17 +340,129 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
     o.m_dev = n_sel;
     o.c[0] = o_cache;
   } else {
-    o.c[0] = out;
+    o.c[0] = bx.x_resid ? o_cache : out;
   }
   if ((e = gemm(ctx, o, s)) != hipSuccess) return fail_hip(ctx, e, "output projection");
 
-  // 7. Keep out and o_cache equal when they are different buffers.
-  if (out != o_cache) {
+  // 7. out = x + O for every row from the refreshed and the cached rows of O, or keep
+  //    out and o_cache equal when they are different buffers.
+  if (bx.x_resid) {
+    e = launch_residual_add(cf.dtype, bx.x_resid, o_cache, out, (long)n_tok * d, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "residual sum");
+  } else if (out != o_cache) {
     e = sel_o ? launch_copy_rows(o_cache, out, n_tok, (int)(d * es), nullptr, nullptr, s)
               : launch_copy_rows(out, o_cache, n_tok, (int)(d * es), nullptr, nullptr, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "output copy");
   }
   return DARE_OK;
+}
+
+}  // namespace
+
+dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch, int seq,
+                            const void* hidden, float* q_prev, void* k_cache, void* v_cache,
+                            void* o_cache, void* out, uint8_t* reuse_mask, int32_t* sel_idx,
+                            int32_t* sel_count, float* scores, void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  dare_status st = check_step_args(ctx, mode, threshold, batch, seq, hidden, q_prev, k_cache, v_cache,
+                                   o_cache, out, reuse_mask);
+  if (st != DARE_OK) return st;
+  return step_impl(ctx, mode, threshold, batch, seq, hidden, q_prev, k_cache, v_cache, o_cache, out,
+                   reuse_mask, sel_idx, sel_count, scores, BlockExtras{nullptr, nullptr}, hip_stream);
+}
+
+namespace {
+// (cos, sin) of pos * base^(-2 i / head_dim) in double precision, rounded to fp32
+void fill_rope_table(float* t, int n_pos, int head_dim, double base) {
+  const int half = head_dim / 2;
+  for (int p = 0; p < n_pos; ++p)
+    for (int i = 0; i < half; ++i) {
+      const double ang = (double)p * std::pow(base, -2.0 * (double)i / (double)head_dim);
+      t[((size_t)p * half + i) * 2 + 0] = (float)std::cos(ang);
+      t[((size_t)p * half + i) * 2 + 1] = (float)std::sin(ang);
+    }
+}
+}  // namespace
+
+dare_status dare_block_attach(dare_ctx* ctx, const dare_block_config* cfg, const void* gain,
+                              const void* bias, void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (!cfg || cfg->struct_size != sizeof(dare_block_config))
+    return fail(ctx, DARE_ERR_INVALID_ARG, "null block config or struct_size mismatch");
+  if (cfg->norm != DARE_NORM_NONE && cfg->norm != DARE_NORM_LAYER && cfg->norm != DARE_NORM_RMS)
+    return fail(ctx, DARE_ERR_INVALID_ARG, "unknown norm kind");
+  if (cfg->norm != DARE_NORM_NONE && !gain) return fail(ctx, DARE_ERR_INVALID_ARG, "norm needs a gain vector");
+  if (cfg->norm != DARE_NORM_NONE && !(cfg->eps >= 0.f)) return fail(ctx, DARE_ERR_INVALID_ARG, "eps must be >= 0");
+  if (cfg->norm != DARE_NORM_LAYER && bias) return fail(ctx, DARE_ERR_INVALID_ARG, "bias is for LayerNorm only");
+  if (!(cfg->rope_base >= 0.f) || std::isinf(cfg->rope_base))
+    return fail(ctx, DARE_ERR_INVALID_ARG, "rope_base must be 0 (off) or a positive number");
+  if (cfg->residual != 0 && cfg->residual != 1) return fail(ctx, DARE_ERR_INVALID_ARG, "residual must be 0 or 1");
+  if (ctx->cfg.hidden % 8 != 0) return fail(ctx, DARE_ERR_UNSUPPORTED, "hidden must be a multiple of 8");
+
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->cfg.device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  // work on the stream may still read the vectors of an earlier attach
+  if ((e = hipStreamSynchronize(s)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+  ctx->has_block = false;
+  const size_t vec_bytes = (size_t)ctx->cfg.hidden * ctx->esize;
+  const size_t max_tok = (size_t)ctx->cfg.max_batch * ctx->cfg.max_seq;
+  auto ensure = [&](void** p, size_t bytes) -> hipError_t {
+    if (*p) return hipSuccess;
+    hipError_t r = hipMalloc(p, bytes);
+    if (r != hipSuccess) *p = nullptr;
+    return r;
+  };
+  if (cfg->norm != DARE_NORM_NONE) {
+    if ((e = ensure(&ctx->gain, vec_bytes)) != hipSuccess) return fail_hip(ctx, e, "hipMalloc");
+    if ((e = ensure(&ctx->h_buf, max_tok * vec_bytes)) != hipSuccess) return fail_hip(ctx, e, "hipMalloc");
+    if ((e = hipMemcpyAsync(ctx->gain, gain, vec_bytes, hipMemcpyDeviceToDevice, s)) != hipSuccess)
+      return fail_hip(ctx, e, "gain copy");
+    if (bias) {
+      if ((e = ensure(&ctx->bias, vec_bytes)) != hipSuccess) return fail_hip(ctx, e, "hipMalloc");
+      if ((e = hipMemcpyAsync(ctx->bias, bias, vec_bytes, hipMemcpyDeviceToDevice, s)) != hipSuccess)
+        return fail_hip(ctx, e, "bias copy");
+    }
+  }
+  if (cfg->rope_base > 0.f) {
+    const size_t elems = (size_t)ctx->cfg.max_seq * ctx->cfg.head_dim;  // (cos, sin) x head_dim / 2
+    if ((e = ensure((void**)&ctx->rope_table, elems * sizeof(float))) != hipSuccess)
+      return fail_hip(ctx, e, "hipMalloc");
+    dare_status st = dare_k_rope_table(ctx->rope_table, ctx->cfg.max_seq, ctx->cfg.head_dim,
+                                       (double)cfg->rope_base);
+    if (st != DARE_OK) return fail(ctx, st, "rotary table");
+  }
+  if ((e = hipStreamSynchronize(s)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+  ctx->block = *cfg;
+  ctx->has_bias = bias != nullptr;
+  ctx->has_block = true;
+  return DARE_OK;
+}
+
+dare_status dare_block_step(dare_ctx* ctx, int mode, float threshold, int batch, int seq, const void* x,
+                            float* q_prev, void* k_cache, void* v_cache, void* o_cache, void* out,
+                            uint8_t* reuse_mask, int32_t* sel_idx, int32_t* sel_count, float* scores,
+                            void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (!ctx->has_block) return fail(ctx, DARE_ERR_INVALID_ARG, "no block attached");
+  dare_status st = check_step_args(ctx, mode, threshold, batch, seq, x, q_prev, k_cache, v_cache, o_cache,
+                                   out, reuse_mask);
+  if (st != DARE_OK) return st;
+  const dare_block_config& bc = ctx->block;
+  if (bc.residual && out == o_cache)
+    return fail(ctx, DARE_ERR_INVALID_ARG, "with the residual sum, out must not be o_cache");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const void* hidden = x;
+  if (bc.norm != DARE_NORM_NONE) {  // Alg. 1/2 line 1
+    hipError_t e = launch_norm(ctx->cfg.dtype, bc.norm, x, ctx->gain, ctx->has_bias ? ctx->bias : nullptr,
+                               bc.eps, batch * seq, ctx->cfg.hidden, ctx->h_buf, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "normalisation");
+    hidden = ctx->h_buf;
+  }
+  BlockExtras bx{bc.rope_base > 0.f ? ctx->rope_table : nullptr, bc.residual ? x : nullptr};
+  return step_impl(ctx, mode, threshold, batch, seq, hidden, q_prev, k_cache, v_cache, o_cache, out,
+                   reuse_mask, sel_idx, sel_count, scores, bx, hip_stream);
 }
 
 // ---------------------------------------------------------------------------
@@ -361,6 +508,71 @@ dare_status dare_k_gemm(int dtype, const void* a, int lda, const void* wt, int n
   g.c32_part_stride = c32_part_stride;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e = dtype == DARE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_gemm_rope(int dtype, const void* a, int lda, const void* wt, int n, int k, int m_max,
+                             const int32_t* idx, const int32_t* m_dev, void* const* c, int ldc, int seg_n,
+                             float* c32, int c32_cols, const float* rope_table, int rope_cols,
+                             int head_dim, int seq, void* hip_stream) {
+  if (!a || !wt || !c || n < 1 || k < 1 || m_max < 0 || lda < k) return DARE_ERR_INVALID_ARG;
+  if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
+  if (seg_n < 1 || n % seg_n != 0 || n / seg_n > 3) return DARE_ERR_INVALID_ARG;
+  if (c32 && (c32_cols < 1 || c32_cols > n || c32_cols % 4 != 0)) return DARE_ERR_INVALID_ARG;
+  if (k % 64 != 0 || n % (dtype == DARE_BF16 ? 64 : 16) != 0 || seg_n % 4 != 0) return DARE_ERR_UNSUPPORTED;
+  if (!rope_table || seq < 1 || head_dim < 4 || head_dim % 4 != 0 || rope_cols < 0 || rope_cols > n ||
+      rope_cols % head_dim != 0 || seg_n % head_dim != 0)
+    return DARE_ERR_INVALID_ARG;
+  GemmArgs g{};
+  g.a = a;
+  g.lda = lda;
+  g.wt = wt;
+  g.n = n;
+  g.k = k;
+  g.m_max = m_max;
+  g.idx = idx;
+  g.m_dev = m_dev;
+  for (int i = 0; i < n / seg_n; ++i) g.c[i] = c[i];
+  g.ldc = ldc;
+  g.seg_n = seg_n;
+  g.c32 = c32;
+  g.c32_cols = c32 ? c32_cols : 0;
+  g.k_parts = 1;
+  g.rope = rope_table;
+  g.rope_cols = rope_cols;
+  g.rope_dh = head_dim;
+  g.rope_seq = seq;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = dtype == DARE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_rope_table(float* table, int n_pos, int head_dim, double base) {
+  if (!table || n_pos < 1 || head_dim < 2 || head_dim % 2 != 0 || !(base > 0.0)) return DARE_ERR_INVALID_ARG;
+  const size_t elems = (size_t)n_pos * head_dim;
+  float* host = new (std::nothrow) float[elems];
+  if (!host) return DARE_ERR_OOM;
+  fill_rope_table(host, n_pos, head_dim, base);
+  hipError_t e = hipMemcpy(table, host, elems * sizeof(float), hipMemcpyHostToDevice);
+  delete[] host;
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_norm(int dtype, int kind, const void* x, const void* gain, const void* bias, float eps,
+                        int n_rows, int d, void* out, void* hip_stream) {
+  if (!x || !gain || !out || n_rows < 0 || d < 8 || d % 8 != 0 || !(eps >= 0.f)) return DARE_ERR_INVALID_ARG;
+  if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
+  if (kind != DARE_NORM_LAYER && kind != DARE_NORM_RMS) return DARE_ERR_INVALID_ARG;
+  if (kind == DARE_NORM_RMS && bias) return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_norm(dtype, kind, x, gain, bias, eps, n_rows, d, out, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+dare_status dare_k_residual_add(int dtype, const void* x, const void* o, void* out, long n_elems,
+                                void* hip_stream) {
+  if (!x || !o || !out || n_elems < 0 || n_elems % 8 != 0) return DARE_ERR_INVALID_ARG;
+  if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
+  hipError_t e = launch_residual_add(dtype, x, o, out, n_elems, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }
 

@@ -38,7 +38,25 @@ struct GemmArgs {
   int c32_cols;
   int k_parts;        // > 1: only c32 is written, as k_parts slabs of partial sums
   long c32_part_stride;
+  // rotary embedding of output columns [0, rope_cols) (fp32 table [pos][head_dim/2]
+  // of (cos, sin) pairs; position of a row = token id % rope_seq); nullptr = none
+  const float* rope;
+  int rope_cols, rope_dh, rope_seq;
 };
+
+// Rotation of the channel pairs (v0, v1) and (v2, v3) of four neighbouring output
+// columns col .. col + 3 (col a multiple of 4) of token tok.
+__device__ __forceinline__ void rope_rotate4(const float* __restrict__ table, int dh, int seq, long tok,
+                                             int col, float& v0, float& v1, float& v2, float& v3) {
+  const int pos = (int)(tok % seq);
+  const f32x4 cs = *reinterpret_cast<const f32x4*>(table + ((long)pos * (dh >> 1) + ((col % dh) >> 1)) * 2);
+  const float a0 = v0 * cs[0] - v1 * cs[1], a1 = v0 * cs[1] + v1 * cs[0];
+  const float a2 = v2 * cs[2] - v3 * cs[3], a3 = v2 * cs[3] + v3 * cs[2];
+  v0 = a0;
+  v1 = a1;
+  v2 = a2;
+  v3 = a3;
+}
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
 
@@ -68,5 +86,9 @@ hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_
 hipError_t launch_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops, hipStream_t s);
 hipError_t launch_copy_rows(const void* src, void* dst, int n_rows, int row_bytes,
                             const int32_t* idx, const int32_t* m_dev, hipStream_t s);
+hipError_t launch_norm(int dtype, int kind, const void* x, const void* gain, const void* bias, float eps,
+                       int n_rows, int d, void* out, hipStream_t s);
+hipError_t launch_residual_add(int dtype, const void* x, const void* o, void* out, long n_elems,
+                               hipStream_t s);
 
 }  // namespace dare

@@ -62,6 +62,8 @@ struct GemmDev {
   int lda, n, k, m_max, ldc, seg_n, c32_cols;
   int k_parts;           // k is cut into this many ranges (1 = whole k per tile)
   long c32_part_stride;  // elements between the fp32 outputs of consecutive ranges
+  const float* rope;     // rotary table, or nullptr
+  int rope_cols, rope_dh, rope_seq;
 };
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -293,21 +295,22 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
       for (int g = 0; g < 4; ++g) {
         const int col = n0 + wave_n * WN + j * 32 + g * 8 + half * 4;
         if (col >= p.n) continue;
-        const float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1];
-        const float v2 = acc[i][j][g * 4 + 2], v3 = acc[i][j][g * 4 + 3];
+        float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1];
+        float v2 = acc[i][j][g * 4 + 2], v3 = acc[i][j][g * 4 + 3];
+        if (c32 && col < p.c32_cols) {  // the scored columns: before any rotation
+          f32x4 o = {v0, v1, v2, v3};
+          *reinterpret_cast<f32x4*>(c32 + tok * p.c32_cols + col) = o;
+        }
         const int seg = col / p.seg_n;
         bf16_t* cbase = seg == 0 ? p.c0 : (seg == 1 ? p.c1 : p.c2);
         if (cbase) {
+          if (p.rope && col < p.rope_cols) rope_rotate4(p.rope, p.rope_dh, p.rope_seq, tok, col, v0, v1, v2, v3);
           bf16x4 o;
           o[0] = (bf16_t)v0;
           o[1] = (bf16_t)v1;
           o[2] = (bf16_t)v2;
           o[3] = (bf16_t)v3;
           *reinterpret_cast<bf16x4*>(cbase + tok * p.ldc + (col - seg * p.seg_n)) = o;
-        }
-        if (c32 && col < p.c32_cols) {
-          f32x4 o = {v0, v1, v2, v3};
-          *reinterpret_cast<f32x4*>(c32 + tok * p.c32_cols + col) = o;
         }
       }
     }
@@ -393,6 +396,10 @@ GemmDev to_dev(const GemmArgs& g) {
   p.c32_cols = g.c32_cols;
   p.k_parts = 1;
   p.c32_part_stride = 0;
+  p.rope = g.rope;
+  p.rope_cols = g.rope_cols;
+  p.rope_dh = g.rope_dh;
+  p.rope_seq = g.rope_seq;
   return p;
 }
 

@@ -19,6 +19,8 @@ struct GemmF32Dev {
   float* c2;
   float* c32;
   int lda, n, k, m_max, ldc, seg_n, c32_cols;
+  const float* rope;
+  int rope_cols, rope_dh, rope_seq;
 };
 
 __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmF32Dev p) {
@@ -74,9 +76,16 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmF32Dev p) {
     const int row = m0 + ty * 4 + i;
     if (row >= m) continue;
     const long tok = p.idx ? (long)p.idx[row] : (long)row;
-    const f32x4 o = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
-    if (cbase) *reinterpret_cast<f32x4*>(cbase + tok * p.ldc + (col - seg * p.seg_n)) = o;
-    if (p.c32 && col < p.c32_cols) *reinterpret_cast<f32x4*>(p.c32 + tok * p.c32_cols + col) = o;
+    float v0 = acc[i][0], v1 = acc[i][1], v2 = acc[i][2], v3 = acc[i][3];
+    if (p.c32 && col < p.c32_cols) {  // the scored columns: before any rotation
+      const f32x4 o = {v0, v1, v2, v3};
+      *reinterpret_cast<f32x4*>(p.c32 + tok * p.c32_cols + col) = o;
+    }
+    if (cbase) {
+      if (p.rope && col < p.rope_cols) rope_rotate4(p.rope, p.rope_dh, p.rope_seq, tok, col, v0, v1, v2, v3);
+      const f32x4 o = {v0, v1, v2, v3};
+      *reinterpret_cast<f32x4*>(cbase + tok * p.ldc + (col - seg * p.seg_n)) = o;
+    }
   }
 }
 
@@ -99,6 +108,10 @@ hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s) {
   p.ldc = g.ldc;
   p.seg_n = g.seg_n;
   p.c32_cols = g.c32_cols;
+  p.rope = g.rope;
+  p.rope_cols = g.rope_cols;
+  p.rope_dh = g.rope_dh;
+  p.rope_seq = g.rope_seq;
   const int tm = (g.m_max + FBM - 1) / FBM, tn = (g.n + FBN - 1) / FBN;
   if (tm == 0 || tn == 0) return hipSuccess;
   hipLaunchKernelGGL(gemm_f32_kernel, dim3(tm, tn), dim3(256), 0, s, p);

@@ -80,6 +80,15 @@ def make_hidden_pair(seed, batch, seq, hidden, fraction, dtype):
             "perturbed": perturbed}
 
 
+def make_norm_params(seed, hidden, dtype):
+    """Gain ~ 1 + 0.1 N(0,1) and bias ~ 0.05 N(0,1) of the normalisation in front of the
+    projections, float32 [hidden] each."""
+    rng = np.random.Generator(np.random.PCG64(seed + 104729))
+    gain = np.float32(1.0) + np.float32(0.1) * rng.standard_normal(hidden, dtype=np.float32)
+    bias = np.float32(0.05) * rng.standard_normal(hidden, dtype=np.float32)
+    return {"gain": _store(gain, dtype), "bias": _store(bias, dtype)}
+
+
 # Layer shapes of the workloads.  "tiny" is the small fp32 case; "llada8b" is one
 # LLaDA-8B-shaped layer at 512 prompt + 512 generated tokens; "llada8b_b8" is the
 # same layer at 2048 tokens and 8 sequences with per-sequence perturbed fractions.
@@ -105,4 +114,5 @@ def make_case(name, seed=1234, fraction=None, **override):
     case = dict(cfg)
     case.update(w)
     case.update(h)
+    case.update(make_norm_params(seed, cfg["hidden"], cfg["dtype"]))
     return case

@@ -1,0 +1,317 @@
+"""GPU parity of the attention block around the layer step: normalisation (Alg. 1/2
+line 1), rotary embedding in the projection's epilogue, residual sum, and
+dare_block_step against the oracle's block_step.
+
+bf16 and the normalised hidden state.  h = norm(x) is a stored bf16 tensor.  The kernel
+rounds fp32 arithmetic to bf16, the oracle float64 arithmetic: about one element in
+20 000 lies so close to a rounding boundary that the two round it to different
+neighbours.  One such element moves a drift score by up to 3e-5, far more than the
+1e-6 band in which scores are compared.  The bf16 block tests therefore check the
+normalisation kernel against the oracle on its own (every element within one bf16 step,
+all but a few in 10 000 identical) and then run the oracle's layer step, rotary
+embedding and residual sum on the h that the kernel produced (the same kernel on the
+same input gives the same bits inside dare_block_step).  The fp32 tests compare with
+the oracle's block_step end to end."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dare_oracle as orc
+from paper_2605_08134_amd import synth
+import parity_util as pu
+from parity_util import assert_close, dev, host, rel_err, store
+
+pytestmark = pytest.mark.gpu
+
+MODES = [orc.MODE_DENSE, orc.MODE_KV, orc.MODE_O, orc.MODE_KVO]
+ROPE_BASE = 10000.0
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_08134_amd import binding
+    binding.lib()
+    return binding
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ------------------------------------------------------------------ stage kernels
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("kind", ["layer", "rms"])
+@pytest.mark.parametrize("rows,d", [(37, 264), (5, 4096), (3, 8192 + 64), (1, 8)])
+def test_norm_kernel(B, dtype, kind, rows, d):
+    r = _rng(rows * d)
+    x = store(r.standard_normal((rows, d)) * 1.7 + 0.3, dtype)
+    gain = store(1.0 + 0.1 * r.standard_normal(d), dtype)
+    bias = store(0.05 * r.standard_normal(d), dtype) if kind == "layer" else None
+    out = torch.full((rows, d), float("nan"), dtype=pu.tdtype(dtype), device="cuda")
+    B.dare_k_norm(kind, dev(x, dtype), dev(gain, dtype), None if bias is None else dev(bias, dtype),
+                  1e-5, out)
+    torch.cuda.synchronize()
+    want = orc.layer_norm(x, gain, bias, 1e-5) if kind == "layer" else orc.rms_norm(x, gain, 1e-5)
+    got = host(out).astype(np.float64)
+    if dtype == "f32":
+        assert np.max(np.abs(got - want)) <= 4e-6 * max(1.0, float(np.max(np.abs(want))))
+    else:
+        # the fp32 result (error about 1e-6 of the value) rounded to the nearest bf16
+        assert np.all(np.abs(got - want) <= pu.half_ulp_bf16(want) + 1e-5 * np.maximum(np.abs(want), 1.0))
+        same = got == orc.round_storage(want, "bf16")
+        assert same.mean() >= 0.999
+
+
+def test_norm_kernel_in_place_and_without_bias(B):
+    r = _rng(9)
+    x = store(r.standard_normal((16, 512)), "f32")
+    gain = store(1.0 + 0.1 * r.standard_normal(512), "f32")
+    xd = dev(x, "f32")
+    B.dare_k_norm("layer", xd, dev(gain, "f32"), None, 1e-6, xd)
+    torch.cuda.synchronize()
+    assert rel_err(host(xd), orc.layer_norm(x, gain, None, 1e-6)) <= 1e-5
+
+
+@pytest.mark.parametrize("head_dim,base,n_pos", [(128, 10000.0, 300), (64, 500000.0, 4096)])
+def test_rope_table(B, head_dim, base, n_pos):
+    t = host(B.dare_k_rope_table(n_pos, head_dim, base))
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    ang = np.arange(n_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / head_dim)[None, :]
+    assert np.max(np.abs(t[:, :, 0] - np.cos(ang))) <= 1e-7
+    assert np.max(np.abs(t[:, :, 1] - np.sin(ang))) <= 1e-7
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("count", [None, 0, 77])
+def test_gemm_rope_epilogue(B, dtype, count):
+    """Q | K | V projection with Q and K rotated, V not; the fp32 copy of the scored
+    columns keeps the unrotated values.  Two sequences: position = token id mod seq."""
+    r = _rng(31 + (count or 0))
+    batch, seq, k, dh, n_heads = 2, 90, 128, 64, 2
+    seg = n_heads * dh
+    n_tok, n = batch * seq, 3 * seg
+    a = store(r.standard_normal((n_tok, k)), dtype)
+    w = store(r.standard_normal((k, n)) * 0.08, dtype)
+    wt = B.dare_k_pack_weight(dev(w, dtype))
+    table = B.dare_k_rope_table(seq + 5, dh, ROPE_BASE)
+    outs = [torch.full((n_tok, seg), 3.0, dtype=wt.dtype, device="cuda") for _ in range(3)]
+    c32 = torch.zeros((n_tok, dh), dtype=torch.float32, device="cuda")
+    if count is None:
+        rows = np.arange(n_tok)
+        B.dare_k_gemm_rope(dev(a, dtype), wt, outs, seg, table, 2 * seg, dh, seq, c32=c32)
+    else:
+        rows = np.sort(r.permutation(n_tok)[:count]).astype(np.int32)
+        idx = np.full(n_tok, 10 ** 6, dtype=np.int32)
+        idx[:count] = rows
+        m_dev = torch.tensor([count], dtype=torch.int32, device="cuda")
+        B.dare_k_gemm_rope(dev(a, dtype), wt, outs, seg, table, 2 * seg, dh, seq, idx=dev(idx),
+                           m_dev=m_dev, m_max=n_tok, c32=c32)
+    torch.cuda.synchronize()
+    y = a.astype(np.float64) @ w.astype(np.float64)
+    pos = (np.arange(n_tok) % seq).astype(np.float64)
+    want = np.concatenate([orc.rope(y[:, :seg], pos, n_heads, ROPE_BASE),
+                           orc.rope(y[:, seg:2 * seg], pos, n_heads, ROPE_BASE), y[:, 2 * seg:]], axis=1)
+    got = np.concatenate([host(o) for o in outs], axis=1)
+    untouched = np.setdiff1d(np.arange(n_tok), rows)
+    assert np.all(got[untouched] == 3.0)
+    if len(rows):
+        assert_close(got[rows], want[rows], dtype)
+        assert rel_err(host(c32)[rows], y[rows, :dh]) <= 2e-6
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n", [8, 264 * 37, 1 << 22])
+def test_residual_add(B, dtype, n):
+    r = _rng(n)
+    x = store(r.standard_normal(n), dtype)
+    o = store(r.standard_normal(n) * 0.3, dtype)
+    out = torch.empty(n, dtype=pu.tdtype(dtype), device="cuda")
+    B.dare_k_residual_add(dev(x, dtype), dev(o, dtype), out)
+    torch.cuda.synchronize()
+    want = x.astype(np.float64) + o.astype(np.float64)
+    got = host(out)
+    if dtype == "f32":
+        assert np.array_equal(got, want.astype(np.float32))
+    else:
+        assert np.array_equal(got.astype(np.float64), orc.round_storage(want, "bf16"))
+
+
+# ------------------------------------------------------------------ the block step
+class GpuBlock(pu.GpuLayer):
+    def __init__(self, case, norm, rope_base, residual, use_bias=True, **kw):
+        super().__init__(case, **kw)
+        self.norm, self.rope_base, self.residual = norm, rope_base, residual
+        self.gain = dev(case["gain"], self.dt) if norm else None
+        self.bias = dev(case["bias"], self.dt) if norm == "layer" and use_bias else None
+        self.layer.block_attach(norm, self.gain, self.bias, 1e-5, rope_base or 0.0, residual)
+
+    def block_step(self, mode, tau, x, state):
+        Bn, T = x.shape[0], x.shape[1]
+        xd = dev(x, self.dt)
+        st = {k: dev(v, None if k == "q_prev" else self.dt) for k, v in state.items()}
+        out = st["o_cache"] if not self.residual else torch.full_like(st["o_cache"], float("nan"))
+        mask = torch.full((Bn, T), 7, dtype=torch.uint8, device="cuda")
+        sel_idx = torch.full((Bn * T,), -1, dtype=torch.int32, device="cuda")
+        sel_count = torch.full((Bn,), -1, dtype=torch.int32, device="cuda")
+        scores = torch.full((Bn, T), float("nan"), dtype=torch.float32, device="cuda")
+        self.layer.block_step(mode, float(tau), xd, st["q_prev"], st["k_cache"], st["v_cache"],
+                              st["o_cache"], out, mask, sel_idx, sel_count, scores)
+        torch.cuda.synchronize()
+        res = {k: host(v) for k, v in st.items()}
+        res.update(block_out=host(out), reuse_mask=host(mask), scores=host(scores),
+                   sel_idx=host(sel_idx), sel_count=host(sel_count))
+        assert torch.equal(xd, dev(x, self.dt))          # the input is never written
+        return res
+
+    def normed(self, x):
+        """h as the normalisation kernel produces it (the block computes the same bits)."""
+        if not self.norm:
+            return np.asarray(x, dtype=np.float32)
+        xd = dev(x, self.dt)
+        h = torch.empty_like(xd)
+        self.B.dare_k_norm(self.norm, xd, self.gain, self.bias, 1e-5, h)
+        torch.cuda.synchronize()
+        return host(h)
+
+
+def _oracle_block(case, gb, state, mode, tau, x, use_bias=True):
+    """The oracle's block step; for bf16 storage on the kernel's own h (see the header)."""
+    storage = "bf16" if case["dtype"] == "bf16" else None
+    bias = case["bias"] if gb.norm == "layer" and use_bias else None
+    args = (case["wq"], case["wk"], case["wv"], case["wo"], state["q_prev"], state["k_cache"],
+            state["v_cache"], state["o_cache"], case["n_heads"])
+    if storage is None:
+        return orc.block_step(mode, tau, x, gb.norm, case["gain"], bias, 1e-5, *args, storage=None,
+                              rope_base=gb.rope_base, residual=gb.residual)
+    h = gb.normed(x)
+    h_or = (orc.layer_norm(x, case["gain"], bias, 1e-5) if gb.norm == "layer" else
+            orc.rms_norm(x, case["gain"], 1e-5) if gb.norm == "rms" else np.asarray(x, dtype=np.float64))
+    assert np.all(np.abs(h - h_or) <= pu.half_ulp_bf16(h_or) + 1e-5 * np.maximum(np.abs(h_or), 1.0))
+    return orc.block_step(mode, tau, h, None, None, None, 0.0, *args, storage="bf16",
+                          rope_base=gb.rope_base, residual=False) | {"x_for_residual": x}
+
+
+def _fill(case, gb, use_bias=True):
+    """Caches after a dense block step on x_prev (K rotated, O before the residual)."""
+    dt = case["dtype"]
+    d, dh = case["hidden"], case["head_dim"]
+    z = np.zeros((case["batch"], case["seq"], d))
+    zero = {"q_prev": np.ones((case["batch"], case["seq"], dh)), "k_cache": z, "v_cache": z, "o_cache": z}
+    r = _oracle_block(case, gb, zero, orc.MODE_DENSE, 0.0, case["x_prev"], use_bias)
+    return {"q_prev": np.asarray(r["q_prev"], dtype=np.float32), "k_cache": store(r["k_cache"], dt),
+            "v_cache": store(r["v_cache"], dt), "o_cache": store(r["out"], dt)}
+
+
+def _check_block(case, gb, got, want, state, mode, tau, x):
+    dt = case["dtype"]
+    layer_view = dict(got, out=got["o_cache"])
+    info = pu.check_step(layer_view, want, state, mode, tau, dt)
+    if "x_for_residual" in want:       # bf16: the oracle ran on the kernel's h; the sum is formed here
+        exact = (np.asarray(x, dtype=np.float64) + want["exact"]["out"]) if gb.residual else want["exact"]["out"]
+    else:
+        exact = want["exact"]["block_out"]
+    if dt == "f32":
+        info["block_out"] = rel_err(got["block_out"], exact)
+        assert info["block_out"] <= 1e-4
+    else:
+        rms_o = float(np.sqrt(np.mean(np.asarray(want["exact"]["out"], dtype=np.float64) ** 2)))
+        ex = np.abs(got["block_out"].astype(np.float64) - exact) - pu.half_ulp_bf16(exact)
+        if gb.residual:                # the stored O carries its own rounding into the sum
+            ex = ex - pu.half_ulp_bf16(want["exact"]["out"])
+        info["block_out"] = float(max(np.max(ex), 0.0)) / rms_o
+        assert info["block_out"] <= pu.TOL["bf16"]
+    if gb.residual:
+        # out is exactly x + stored O, row by row, reused rows included
+        o = got["o_cache"].astype(np.float64)
+        s = np.asarray(x, dtype=np.float64) + o
+        want_sum = s.astype(np.float32) if dt == "f32" else orc.round_storage(s, "bf16")
+        assert np.array_equal(got["block_out"].astype(np.float64), np.asarray(want_sum, dtype=np.float64))
+    return info
+
+
+@pytest.mark.parametrize("norm,rope,residual", [("rms", ROPE_BASE, True), ("layer", None, True),
+                                                (None, ROPE_BASE, False), ("layer", ROPE_BASE, False)])
+@pytest.mark.parametrize("mode", MODES)
+def test_block_tiny_fp32(norm, rope, residual, mode):
+    case = synth.make_case("tiny", seed=1234, batch=2, seq=75)
+    gb = GpuBlock(case, norm, rope, residual)
+    state = _fill(case, gb)
+    for tau in (-1.0, synth.TAU_SEPARATING, 2.5):
+        want = _oracle_block(case, gb, state, mode, tau, case["x_cur"])
+        got = gb.block_step(mode, tau, case["x_cur"], state)
+        _check_block(case, gb, got, want, state, mode, tau, case["x_cur"])
+    gb.layer.destroy()
+
+
+@pytest.mark.parametrize("shape", [
+    dict(batch=2, seq=320, hidden=512, n_heads=4, head_dim=128, fraction=0.2),
+    dict(batch=3, seq=100, hidden=256, n_heads=4, head_dim=64, fraction=(0.05, 0.5)),
+])
+@pytest.mark.parametrize("norm", ["rms", "layer"])
+@pytest.mark.parametrize("mode", MODES)
+def test_block_small_bf16(shape, norm, mode):
+    case = synth.make_case("llada8b", seed=78, **shape)
+    gb = GpuBlock(case, norm, ROPE_BASE, True, max_batch=case["batch"] + 1, max_seq=case["seq"] + 9)
+    state = _fill(case, gb)
+    s = _oracle_block(case, gb, state, orc.MODE_KV, 0.0, case["x_cur"])["scores"]
+    for tau in (-1.0, pu.gap_threshold(s, 0.6), 2.5):
+        want = _oracle_block(case, gb, state, mode, tau, case["x_cur"])
+        got = gb.block_step(mode, tau, case["x_cur"], state)
+        _check_block(case, gb, got, want, state, mode, tau, case["x_cur"])
+    gb.layer.destroy()
+
+
+def test_block_without_bias_and_reattach():
+    case = synth.make_case("tiny", seed=3)
+    gb = GpuBlock(case, "layer", None, True, use_bias=False)
+    state = _fill(case, gb, use_bias=False)
+    want = _oracle_block(case, gb, state, orc.MODE_KVO, synth.TAU_SEPARATING, case["x_cur"], use_bias=False)
+    got = gb.block_step(orc.MODE_KVO, synth.TAU_SEPARATING, case["x_cur"], state)
+    _check_block(case, gb, got, want, state, orc.MODE_KVO, synth.TAU_SEPARATING, case["x_cur"])
+    # a second attach replaces the first
+    gb.norm, gb.rope_base = "rms", ROPE_BASE
+    gb.bias = None
+    gb.layer.block_attach("rms", gb.gain, None, 1e-5, ROPE_BASE, True)
+    state = _fill(case, gb)
+    want = _oracle_block(case, gb, state, orc.MODE_KV, synth.TAU_SEPARATING, case["x_cur"])
+    got = gb.block_step(orc.MODE_KV, synth.TAU_SEPARATING, case["x_cur"], state)
+    _check_block(case, gb, got, want, state, orc.MODE_KV, synth.TAU_SEPARATING, case["x_cur"])
+    gb.layer.destroy()
+
+
+def test_block_argument_errors():
+    case = synth.make_case("tiny", seed=3)
+    gl = pu.GpuLayer(case)
+    Bm = gl.B
+    x = dev(case["x_cur"], "f32")
+    st = gl.layer.new_state(1, 128)
+    mask = torch.zeros((1, 128), dtype=torch.uint8, device="cuda")
+    out = torch.zeros_like(st["o_cache"])
+    with pytest.raises(Bm.DareError) as ei:        # nothing attached yet
+        gl.layer.block_step(1, 0.1, x, st["q_prev"], st["k_cache"], st["v_cache"], st["o_cache"], out, mask)
+    assert ei.value.status == Bm.DARE_ERR_INVALID_ARG
+    with pytest.raises(Bm.DareError):              # norm without gain
+        gl.layer.block_attach("rms", None, None)
+    with pytest.raises(Bm.DareError):              # bias with the RMS variant
+        gl.layer.block_attach("rms", dev(case["gain"], "f32"), dev(case["bias"], "f32"))
+    gl.layer.block_attach("rms", dev(case["gain"], "f32"), None, 1e-5, ROPE_BASE, True)
+    with pytest.raises(Bm.DareError):              # residual: out must not alias o_cache
+        gl.layer.block_step(1, 0.1, x, st["q_prev"], st["k_cache"], st["v_cache"], st["o_cache"],
+                            st["o_cache"], mask)
+    gl.layer.destroy()
+
+
+def test_block_llada8b_full_size():
+    """LLaDA-8B-shaped block: RMS normalisation, rotary embedding, residual sum."""
+    case = synth.make_case("llada8b", seed=1234, fraction=0.20)
+    gb = GpuBlock(case, "rms", ROPE_BASE, True)
+    state = _fill(case, gb)
+    tau = synth.TAU_SEPARATING
+    for mode in (orc.MODE_DENSE, orc.MODE_KVO):
+        want = _oracle_block(case, gb, state, mode, tau, case["x_cur"])
+        got = gb.block_step(mode, tau, case["x_cur"], state)
+        info = _check_block(case, gb, got, want, state, mode, tau, case["x_cur"])
+        if mode != orc.MODE_DENSE:
+            assert np.array_equal(got["reuse_mask"].astype(bool), ~case["perturbed"])
+        print("llada8b block mode %d errors: %s" % (mode, info))
+    gb.layer.destroy()
