@@ -52,6 +52,20 @@ Readings taken where the paper is silent or has two forms:
     the same up to rounding); the output cache holds the attention block's output
     before the residual sum, and ``out = x + O`` is formed for every row from the
     current hidden state.
+  * thresholds from reuse rates (Sec. 3.1, "Reuse rate allocation").  The threshold of a
+    layer is "the drift score corresponding to the phi-quantile": read as the order
+    statistic s_(k), k = ceil(phi * T), of the T scores of one sequence at the current
+    step (per sequence, so sequences stay independent; "reuse rates are computed
+    dynamically at runtime", Sec. 5).  With the rule s <= tau this reuses the k tokens
+    of smallest drift (and whatever ties with the k-th).  phi = 0 gives tau = -inf
+    (nothing reused).  NaN scores sort last and are never reused: a NaN order
+    statistic is replaced by +inf.  k is computed from phi as a float32 number widened
+    to double.  ``allocate_quantiles`` is the layer-wise formula
+    phi_l = L phi_bar softmax(-s_l / eps) with s_l the mean drift of layer l over tokens
+    and steps (Sec. 3.1 eq. 2 of that paragraph); values above 1 are cut to 1 (a
+    quantile cannot exceed 1; the paper does not say).  ``policy_mode`` is the
+    host-side schedule of Sec. 5 (Fast-dLLM-v2 setting): the first layers are not
+    reused at all and every r-th step recomputes everything.
   * precision.  The paper runs in BF16 (Sec. 5, App. A): the tensors its
     algorithms name -- Q, K, V, the attention rows before Wo, the layer output --
     are bf16 tensors, with wide accumulation inside each product.  ``storage=None``
@@ -119,6 +133,43 @@ def reuse_decision(scores, tau):
     t32 = np.float32(tau)
     with np.errstate(invalid="ignore"):
         return s32 <= t32
+
+
+def quantile_threshold(scores, phi):
+    """Sec. 3.1: per sequence, the drift score at the phi-quantile = the k-th smallest
+    of the T scores, k = ceil(phi * T).  scores [B, T]; returns float32 tau [B]
+    (-inf when k = 0; +inf when the k-th smallest is NaN)."""
+    s32 = np.asarray(scores, dtype=np.float64).astype(np.float32)
+    B, T = s32.shape
+    k = int(np.ceil(np.float64(np.float32(phi)) * T))
+    if not 0 <= k <= T:
+        raise ValueError("phi must lie in [0, 1]")
+    tau = np.full(B, -np.inf, dtype=np.float32)
+    if k > 0:
+        srt = np.sort(s32, axis=1)              # NaN sorts last
+        tau = srt[:, k - 1].copy()
+        tau[np.isnan(tau)] = np.inf
+    return tau
+
+
+def allocate_quantiles(s_layers, phi_bar, eps):
+    """Sec. 3.1: phi_l = (L phi_bar) softmax(-s_l / eps) over the L layers, cut to [0, 1]."""
+    s = _f64(s_layers)
+    z = -s / float(eps)
+    w = np.exp(z - np.max(z))
+    phi = len(s) * float(phi_bar) * w / np.sum(w)
+    return np.minimum(phi, 1.0)
+
+
+def policy_mode(mode, layer, step, skip_layers=0, refresh_interval=0):
+    """Sec. 5 (Fast-dLLM-v2 setting): layers [0, skip_layers) always recompute, and
+    with a refresh interval r > 0 every step whose index is a multiple of r recomputes
+    everything; otherwise the requested mode stands."""
+    if layer < skip_layers:
+        return MODE_DENSE
+    if refresh_interval > 0 and step % refresh_interval == 0:
+        return MODE_DENSE
+    return mode
 
 
 def selection(reuse):
@@ -202,13 +253,15 @@ def rope(x, positions, n_heads, base=10000.0):
 
 
 def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
-               n_heads, score_head=0, storage=None, rope_base=None):
+               n_heads, score_head=0, storage=None, rope_base=None, quantile=False):
     """One step of the layer in mode DENSE / KV (Alg. 1) / O (Alg. 2) / KVO.
 
     x [B,T,d]; w* [d,d]; q_prev [B,T,Dh] (or [B,T,d] when score_head = -1);
     k_cache, v_cache, o_cache [B,T,d] hold the previous step's state.
     rope_base: None, or the base of the rotary embedding applied to Q and to the K rows
     projected at this step (see the header).
+    quantile: tau is a reuse rate phi in [0, 1]; each sequence's threshold is
+    quantile_threshold of its scores (returned as "tau", float32 [B]).
     Returns a dict with out, k_cache, v_cache, o_cache, q_prev (all updated,
     float64), scores [B,T] float64, reuse_mask uint8 [B,T] (1 = reused),
     sel_idx, sel_count, sel_off, and exact = {out, k_cache, v_cache} before the
@@ -229,10 +282,14 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
     scores = drift_scores(q_sc, _f64(q_prev))
 
     # Alg. 1/2 lines 4-5.
+    if quantile:
+        tau_b = quantile_threshold(scores, tau)
+    else:
+        tau_b = np.full(B, np.float32(tau), dtype=np.float32)
     if mode == MODE_DENSE:
         reuse = np.zeros((B, T), dtype=bool)
     else:
-        reuse = reuse_decision(scores, tau)
+        reuse = np.stack([reuse_decision(scores[b], tau_b[b]) for b in range(B)])
     sel_idx, sel_count, sel_off = selection(reuse)
     # rotary embedding of queries and of the keys projected at this step (position =
     # index in the sequence); the score above used the unrotated query
@@ -281,6 +338,7 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
         "exact": {"out": out_exact, "k_cache": K_exact, "v_cache": V_exact},
         "q_prev": q_sc.copy(),
         "scores": scores,
+        "tau": tau_b,
         "reuse_mask": reuse.astype(np.uint8),
         "sel_idx": sel_idx,
         "sel_count": sel_count,
@@ -290,7 +348,7 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
 
 def block_step(mode, tau, x, norm, gain, bias, eps, wq, wk, wv, wo, q_prev, k_cache,
                v_cache, o_cache, n_heads, score_head=0, storage=None, rope_base=None,
-               residual=True):
+               residual=True, quantile=False):
     """The attention block around ``layer_step``: h = norm(x) (Alg. 1/2 line 1; norm is
     "layer", "rms" or None), the layer step on h, then out = x + O when residual.
 
@@ -308,7 +366,8 @@ def block_step(mode, tau, x, norm, gain, bias, eps, wq, wk, wv, wo, q_prev, k_ca
         raise ValueError("norm must be 'layer', 'rms' or None")
     h = round_storage(h, storage)          # the normalised hidden state is a stored tensor
     r = layer_step(mode, tau, h, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
-                   n_heads, score_head=score_head, storage=storage, rope_base=rope_base)
+                   n_heads, score_head=score_head, storage=storage, rope_base=rope_base,
+                   quantile=quantile)
     r["h"] = h
     exact_block = x + r["out"] if residual else r["out"].copy()
     r["exact"]["block_out"] = exact_block
