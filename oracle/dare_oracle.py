@@ -59,8 +59,9 @@ Readings taken where the paper is silent or has two forms:
     dynamically at runtime", Sec. 5).  With the rule s <= tau this reuses the k tokens
     of smallest drift (and whatever ties with the k-th).  phi = 0 gives tau = -inf
     (nothing reused).  NaN scores sort last and are never reused: a NaN order
-    statistic is replaced by +inf.  k is computed from phi as a float32 number widened
-    to double.  ``allocate_quantiles`` is the layer-wise formula
+    statistic is replaced by +inf.  k = ceil(phi * T) with the product formed in
+    float32 (phi and T as float32 numbers, one rounding), so that a rate such as 0.3,
+    which is not a binary fraction, times 40 tokens gives 12 and not 13.  ``allocate_quantiles`` is the layer-wise formula
     phi_l = L phi_bar softmax(-s_l / eps) with s_l the mean drift of layer l over tokens
     and steps (Sec. 3.1 eq. 2 of that paragraph); values above 1 are cut to 1 (a
     quantile cannot exceed 1; the paper does not say).  ``policy_mode`` is the
@@ -141,7 +142,7 @@ def quantile_threshold(scores, phi):
     (-inf when k = 0; +inf when the k-th smallest is NaN)."""
     s32 = np.asarray(scores, dtype=np.float64).astype(np.float32)
     B, T = s32.shape
-    k = int(np.ceil(np.float64(np.float32(phi)) * T))
+    k = int(np.ceil(np.float32(phi) * np.float32(T)))
     if not 0 <= k <= T:
         raise ValueError("phi must lie in [0, 1]")
     tau = np.full(B, -np.inf, dtype=np.float32)

@@ -25,12 +25,20 @@ def test_quantile_threshold_counting_definition(T, phi):
     # tau is the smallest score with at least ceil(phi T) scores <= it
     s = _rng(T).standard_normal((4, T)).astype(np.float32)
     tau = orc.quantile_threshold(s, phi)
-    k = int(np.ceil(np.float64(np.float32(phi)) * T))
+    k = int(np.ceil(np.float32(phi) * np.float32(T)))
     for b in range(4):
         assert (s[b] <= tau[b]).sum() >= k
         assert (s[b] < tau[b]).sum() < k
         assert tau[b] in s[b]
         assert orc.reuse_decision(s[b], tau[b]).sum() == k        # distinct scores: exactly k reused
+
+
+@pytest.mark.parametrize("phi,T,k", [(0.3, 40, 12), (0.25, 100, 25), (0.7, 10, 7), (0.1, 1000, 100),
+                                     (0.301, 1000, 301), (0.3001, 40, 13), (1.0, 33, 33)])
+def test_quantile_rank_of_decimal_rates(phi, T, k):
+    # the rank is the count a person expects from the decimal rate
+    s = np.arange(T, dtype=np.float32)[None, ::-1].copy()
+    assert orc.quantile_threshold(s, phi)[0] == np.float32(k - 1)
 
 
 def test_quantile_threshold_edge_cases():
