@@ -164,6 +164,55 @@ dare_status dare_block_step(dare_ctx* ctx, int mode, float threshold, int batch,
                             uint8_t* reuse_mask, int32_t* sel_idx, int32_t* sel_count,
                             float* scores, void* hip_stream);
 
+/*
+ * Thresholds from reuse rates (Sec. 3.1, "Reuse rate allocation").
+ *
+ * Rule DARE_RULE_SCORE (default): the `threshold` argument of the step calls is the
+ * drift score tau itself.  Rule DARE_RULE_QUANTILE: it is a reuse rate phi in [0, 1],
+ * and each sequence's tau is "the drift score at the phi-quantile" of its own scores at
+ * this step: the k-th smallest, k = ceil(phi * seq) with the product formed in fp32
+ * (phi = 0: tau = -inf, nothing reused; scores that tie with the k-th are reused too;
+ * NaN scores sort last, and if the k-th smallest is NaN tau is +inf).  The selection is
+ * exact (radix select on the device); tau never travels to the host.  A phi outside
+ * [0, 1] is INVALID_ARG at the step call.
+ */
+enum { DARE_RULE_SCORE = 0, DARE_RULE_QUANTILE = 1 };
+dare_status dare_set_threshold_rule(dare_ctx* ctx, int rule);
+
+/*
+ * Copy the tau that each sequence used in the last step under DARE_RULE_QUANTILE into
+ * dst (device memory, [batch] fp32, batch <= max_batch); enqueued on the stream, no
+ * synchronisation.  INVALID_ARG before the rule was first set.
+ */
+dare_status dare_get_thresholds(dare_ctx* ctx, float* dst, int batch, void* hip_stream);
+
+/*
+ * Running layer-wise drift score s_l = mean over tokens and steps of the drift score
+ * (Sec. 3.1 eq. 2 of "Reuse rate allocation").  enable(on = 1) zeroes the
+ * accumulators and makes every later step (any mode, any rule) add its scores: one
+ * fp64 sum and one count on the device, NaN scores left out.  read() synchronises the
+ * stream and returns mean (0 if count is 0) and count.  Costs one small kernel per step
+ * while enabled under DARE_RULE_SCORE, nothing extra under DARE_RULE_QUANTILE.
+ */
+dare_status dare_drift_stats_enable(dare_ctx* ctx, int on, void* hip_stream);
+dare_status dare_drift_stats_read(dare_ctx* ctx, double* mean, int64_t* count,
+                                  void* hip_stream);
+
+/*
+ * Layer-wise reuse rates (same section): phi_out[l] = min(1, n_layers * phi_bar *
+ * softmax(-s / eps)[l]).  Host arrays of n_layers doubles; no GPU work.
+ * INVALID_ARG for n_layers < 1, eps <= 0, phi_bar outside [0, 1] or a NaN.
+ */
+dare_status dare_allocate_quantiles(int n_layers, const double* s, double phi_bar,
+                                    double eps, double* phi_out);
+
+/*
+ * The schedule of Sec. 5 (Fast-dLLM-v2 setting), host only: returns DARE_MODE_DENSE
+ * for layers [0, skip_layers) and, when refresh_interval > 0, for every step whose
+ * index is a multiple of it; else `mode`.
+ */
+int dare_policy_mode(int mode, int layer, int step, int skip_layers, int refresh_interval);
+
 /* Free a context and its device memory.  NULL is a no-op. */
 dare_status dare_destroy(dare_ctx* ctx);
 

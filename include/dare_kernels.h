@@ -107,6 +107,19 @@ dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows,
                              const int32_t* m_dev, void* hip_stream);
 
 /*
+ * Threshold from a reuse rate and the decision under it (Sec. 3.1 "Reuse rate
+ * allocation"; rule as dare_set_threshold_rule in dare.h).  scores [batch, seq] fp32.
+ * phi in [0, 1]: per sequence tau = k-th smallest score, k = ceil(phi * seq) in fp32;
+ * writes tau_out[batch] (optional) and mask[batch, seq] = (score <= tau), all 0 when
+ * force_refresh.  phi < 0: statistics only, mask and tau_out are not touched.
+ * stat_sum / stat_count (both or neither): device accumulators to which the sum and the
+ * number of the non-NaN scores are added atomically.
+ */
+dare_status dare_k_quantile_mask(const float* scores, int batch, int seq, float phi,
+                                 int force_refresh, float* tau_out, uint8_t* mask,
+                                 double* stat_sum, uint64_t* stat_count, void* hip_stream);
+
+/*
  * The projection above with the rotary embedding in its epilogue (see dare_block_config
  * in dare.h): output columns [0, rope_cols) are rotated, channel pair (2i, 2i+1) of
  * every head_dim-wide head by the angle whose (cos, sin) is

@@ -23,7 +23,10 @@ EXPORTS = (
     "dare_k_attention", "dare_k_copy_rows", "dare_k_calib_mfma",
     "dare_block_attach", "dare_block_step", "dare_k_gemm_rope", "dare_k_rope_table",
     "dare_k_norm", "dare_k_residual_add",
+    "dare_set_threshold_rule", "dare_get_thresholds", "dare_drift_stats_enable", "dare_drift_stats_read",
+    "dare_allocate_quantiles", "dare_policy_mode", "dare_k_quantile_mask",
 )
+RULE_SCORE, RULE_QUANTILE = 0, 1
 NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2
 NORM_KINDS = {None: NORM_NONE, "layer": NORM_LAYER, "rms": NORM_RMS}
 
@@ -109,6 +112,21 @@ def lib():
     L.dare_k_norm.restype = i32
     L.dare_k_residual_add.argtypes = [i32, vp, vp, vp, ctypes.c_long, vp]
     L.dare_k_residual_add.restype = i32
+    dbl_p = ctypes.POINTER(ctypes.c_double)
+    L.dare_set_threshold_rule.argtypes = [vp, i32]
+    L.dare_set_threshold_rule.restype = i32
+    L.dare_get_thresholds.argtypes = [vp, vp, i32, vp]
+    L.dare_get_thresholds.restype = i32
+    L.dare_drift_stats_enable.argtypes = [vp, i32, vp]
+    L.dare_drift_stats_enable.restype = i32
+    L.dare_drift_stats_read.argtypes = [vp, dbl_p, ctypes.POINTER(ctypes.c_int64), vp]
+    L.dare_drift_stats_read.restype = i32
+    L.dare_allocate_quantiles.argtypes = [i32, dbl_p, ctypes.c_double, ctypes.c_double, dbl_p]
+    L.dare_allocate_quantiles.restype = i32
+    L.dare_policy_mode.argtypes = [i32] * 5
+    L.dare_policy_mode.restype = i32
+    L.dare_k_quantile_mask.argtypes = [vp, i32, i32, f32, i32, vp, vp, vp, vp, vp]
+    L.dare_k_quantile_mask.restype = i32
     _lib = L
     return L
 
@@ -201,6 +219,25 @@ class DareLayer:
                                    _stream(stream))
         _check(st, self._ctx)
 
+    def set_threshold_rule(self, rule):
+        _check(lib().dare_set_threshold_rule(self._ctx, rule), self._ctx)
+
+    def thresholds(self, batch, stream=None):
+        """The per-sequence thresholds of the last quantile step (float32 tensor [batch])."""
+        import torch
+        out = torch.empty(batch, dtype=torch.float32, device=self.device)
+        _check(lib().dare_get_thresholds(self._ctx, _ptr(out), batch, _stream(stream)), self._ctx)
+        return out
+
+    def drift_stats_enable(self, on=True, stream=None):
+        _check(lib().dare_drift_stats_enable(self._ctx, int(bool(on)), _stream(stream)), self._ctx)
+
+    def drift_stats_read(self, stream=None):
+        mean, count = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(lib().dare_drift_stats_read(self._ctx, ctypes.byref(mean), ctypes.byref(count),
+                                           _stream(stream)), self._ctx)
+        return mean.value, count.value
+
     def destroy(self):
         if self._ctx:
             lib().dare_destroy(self._ctx)
@@ -211,6 +248,18 @@ class DareLayer:
             self.destroy()
         except Exception:
             pass
+
+
+def dare_allocate_quantiles(s_layers, phi_bar, eps):
+    n = len(s_layers)
+    src = (ctypes.c_double * n)(*[float(v) for v in s_layers])
+    out = (ctypes.c_double * n)()
+    _check(lib().dare_allocate_quantiles(n, src, float(phi_bar), float(eps), out))
+    return list(out)
+
+
+def dare_policy_mode(mode, layer, step, skip_layers=0, refresh_interval=0):
+    return lib().dare_policy_mode(mode, layer, step, skip_layers, refresh_interval)
 
 
 # ---- kernel-level entry points ---------------------------------------------------------
@@ -235,6 +284,13 @@ def dare_k_gemm(a, wt, outs, seg_n, idx=None, m_dev=None, m_max=None, c32=None, 
     _check(lib().dare_k_gemm(dtype, _ptr(a), a.shape[-1], _ptr(wt), n, k, m_max, _ptr(idx), _ptr(m_dev),
                              arr, ldc, seg_n, _ptr(c32), 0 if c32 is None else c32.shape[-1],
                              k_parts, 0 if c32 is None else m_max * c32.shape[-1], _stream(stream)))
+
+
+def dare_k_quantile_mask(scores, phi, mask, tau_out=None, force_refresh=False, stat_sum=None,
+                         stat_count=None, stream=None):
+    batch, seq = scores.shape
+    _check(lib().dare_k_quantile_mask(_ptr(scores), batch, seq, phi, int(force_refresh), _ptr(tau_out),
+                                      _ptr(mask), _ptr(stat_sum), _ptr(stat_count), _stream(stream)))
 
 
 def dare_k_gemm_rope(a, wt, outs, seg_n, rope_table, rope_cols, head_dim, seq, idx=None, m_dev=None,

@@ -33,6 +33,12 @@ struct dare_ctx {
   void* bias;          // [d] or nullptr
   void* h_buf;         // [max tokens, d] normalised hidden state
   float* rope_table;   // [max_seq, head_dim / 2, 2] (cos, sin), or nullptr
+  // thresholds from reuse rates and drift statistics
+  int rule;            // DARE_RULE_SCORE or DARE_RULE_QUANTILE
+  bool stats_on;
+  float* tau_dev;      // [max_batch] thresholds of the last quantile step
+  float* scores_buf;   // [max tokens] scores when the caller passes none
+  double* stat_sum;    // one fp64 sum followed by one 64-bit count
   std::string err;
 };
 
@@ -77,7 +83,8 @@ struct DeviceGuard {
 void free_ctx(dare_ctx* c) {
   if (!c) return;
   void* bufs[] = {c->wqkv_t, c->wo_t, c->q_buf, c->attn_buf, c->q_new, c->sel_idx, c->sel_off,
-                  c->attn_work, c->gain, c->bias, c->h_buf, c->rope_table};
+                  c->attn_work, c->gain, c->bias, c->h_buf, c->rope_table, c->tau_dev, c->scores_buf,
+                  c->stat_sum};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   delete c;
@@ -138,6 +145,10 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, 
   c->has_block = c->has_bias = false;
   c->gain = c->bias = c->h_buf = nullptr;
   c->rope_table = nullptr;
+  c->rule = DARE_RULE_SCORE;
+  c->stats_on = false;
+  c->tau_dev = c->scores_buf = nullptr;
+  c->stat_sum = nullptr;
   const size_t d = cfg->hidden;
   c->attn_work_bytes = cfg->dtype == DARE_BF16
                            ? attn_bf16_work_bytes(cfg->max_batch, cfg->max_seq, cfg->n_heads, cfg->head_dim)
@@ -203,6 +214,8 @@ dare_status check_step_args(dare_ctx* ctx, int mode, float threshold, int batch,
   if (batch > ctx->cfg.max_batch || seq > ctx->cfg.max_seq)
     return fail(ctx, DARE_ERR_INVALID_ARG, "batch or seq exceeds the context's maximum");
   if (std::isnan(threshold)) return fail(ctx, DARE_ERR_INVALID_ARG, "threshold is NaN");
+  if (ctx->rule == DARE_RULE_QUANTILE && !(threshold >= 0.f && threshold <= 1.f))
+    return fail(ctx, DARE_ERR_INVALID_ARG, "under the quantile rule the threshold is a reuse rate in [0, 1]");
   return DARE_OK;
 }
 
@@ -264,11 +277,22 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
   }
   if ((e = gemm(ctx, g, s)) != hipSuccess) return fail_hip(ctx, e, "query projection");
 
-  // 2. Drift score, reuse decision, score-cache update (Alg. 1/2 lines 3-5).
-  e = launch_score(ctx->q_new, sw, sw, k_parts, (long)n_tok * sw, q_prev, n_tok, threshold,
-                   mode == DARE_MODE_DENSE, scores,
-                   nullptr, reuse_mask, s);
+  // 2. Drift score, reuse decision, score-cache update (Alg. 1/2 lines 3-5).  Under the
+  //    quantile rule the score kernel's decision is replaced by the one the select
+  //    kernel takes; with statistics on, that kernel also (or only) adds up the scores.
+  const bool by_rate = ctx->rule == DARE_RULE_QUANTILE;
+  float* sc = scores;
+  if (!sc && (by_rate || ctx->stats_on)) sc = ctx->scores_buf;
+  e = launch_score(ctx->q_new, sw, sw, k_parts, (long)n_tok * sw, q_prev, n_tok, by_rate ? 0.f : threshold,
+                   mode == DARE_MODE_DENSE || by_rate, sc, nullptr, reuse_mask, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "score");
+  if (by_rate || ctx->stats_on) {
+    const int rank = by_rate ? (int)ceilf(threshold * (float)seq) : -1;
+    double* sum = ctx->stats_on ? ctx->stat_sum : nullptr;
+    e = launch_quantile_mask(sc, batch, seq, rank, mode == DARE_MODE_DENSE, ctx->tau_dev, reuse_mask, sum,
+                             reinterpret_cast<unsigned long long*>(sum ? sum + 1 : nullptr), s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "threshold selection");
+  }
 
   // 3. Index list of the refreshed tokens.
   if (mode != DARE_MODE_DENSE || sel_idx || sel_count) {
@@ -508,6 +532,124 @@ dare_status dare_k_gemm(int dtype, const void* a, int lda, const void* wt, int n
   g.c32_part_stride = c32_part_stride;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e = dtype == DARE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
+}
+
+namespace {
+// scratch of the threshold rule and the statistics, allocated on first use
+dare_status ensure_threshold_buffers(dare_ctx* ctx) {
+  const size_t max_tok = (size_t)ctx->cfg.max_batch * ctx->cfg.max_seq;
+  struct { void** p; size_t bytes; } need[] = {
+      {(void**)&ctx->tau_dev, (size_t)ctx->cfg.max_batch * sizeof(float)},
+      {(void**)&ctx->scores_buf, max_tok * sizeof(float)},
+      {(void**)&ctx->stat_sum, 2 * sizeof(double)},
+  };
+  for (auto& n : need) {
+    if (*n.p) continue;
+    hipError_t e = hipMalloc(n.p, n.bytes);
+    if (e != hipSuccess) {
+      *n.p = nullptr;
+      return fail_hip(ctx, e, "hipMalloc");
+    }
+    if ((e = hipMemset(*n.p, 0, n.bytes)) != hipSuccess) return fail_hip(ctx, e, "hipMemset");
+  }
+  return DARE_OK;
+}
+}  // namespace
+
+dare_status dare_set_threshold_rule(dare_ctx* ctx, int rule) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (rule != DARE_RULE_SCORE && rule != DARE_RULE_QUANTILE) return fail(ctx, DARE_ERR_INVALID_ARG, "unknown rule");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->cfg.device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  dare_status st = ensure_threshold_buffers(ctx);
+  if (st != DARE_OK) return st;
+  ctx->rule = rule;
+  return DARE_OK;
+}
+
+dare_status dare_get_thresholds(dare_ctx* ctx, float* dst, int batch, void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (!dst || batch < 1 || batch > ctx->cfg.max_batch) return fail(ctx, DARE_ERR_INVALID_ARG, "bad dst or batch");
+  if (!ctx->tau_dev) return fail(ctx, DARE_ERR_INVALID_ARG, "no threshold rule was set on this context");
+  hipError_t e = hipMemcpyAsync(dst, ctx->tau_dev, (size_t)batch * sizeof(float), hipMemcpyDeviceToDevice,
+                                static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? DARE_OK : fail_hip(ctx, e, "hipMemcpyAsync");
+}
+
+dare_status dare_drift_stats_enable(dare_ctx* ctx, int on, void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (on != 0 && on != 1) return fail(ctx, DARE_ERR_INVALID_ARG, "on must be 0 or 1");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->cfg.device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  if (on) {
+    dare_status st = ensure_threshold_buffers(ctx);
+    if (st != DARE_OK) return st;
+    // ordered on the stream after the steps already enqueued
+    e = hipMemsetAsync(ctx->stat_sum, 0, 2 * sizeof(double), static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipMemsetAsync");
+  }
+  ctx->stats_on = on != 0;
+  return DARE_OK;
+}
+
+dare_status dare_drift_stats_read(dare_ctx* ctx, double* mean, int64_t* count, void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (!mean || !count) return fail(ctx, DARE_ERR_INVALID_ARG, "null output pointer");
+  if (!ctx->stat_sum) return fail(ctx, DARE_ERR_INVALID_ARG, "statistics were never enabled");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->cfg.device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  double host[2];
+  if ((e = hipMemcpyAsync(host, ctx->stat_sum, sizeof(host), hipMemcpyDeviceToHost, s)) != hipSuccess)
+    return fail_hip(ctx, e, "hipMemcpyAsync");
+  if ((e = hipStreamSynchronize(s)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+  uint64_t n;
+  std::memcpy(&n, &host[1], sizeof(n));
+  *count = (int64_t)n;
+  *mean = n ? host[0] / (double)n : 0.0;
+  return DARE_OK;
+}
+
+dare_status dare_allocate_quantiles(int n_layers, const double* s, double phi_bar, double eps,
+                                    double* phi_out) {
+  if (n_layers < 1 || !s || !phi_out || !(eps > 0.0) || !(phi_bar >= 0.0 && phi_bar <= 1.0))
+    return DARE_ERR_INVALID_ARG;
+  double zmax = -INFINITY;
+  for (int l = 0; l < n_layers; ++l) {
+    if (std::isnan(s[l])) return DARE_ERR_INVALID_ARG;
+    const double z = -s[l] / eps;
+    if (z > zmax) zmax = z;
+  }
+  double den = 0.0;
+  for (int l = 0; l < n_layers; ++l) den += std::exp(-s[l] / eps - zmax);
+  for (int l = 0; l < n_layers; ++l) {
+    const double phi = (double)n_layers * phi_bar * std::exp(-s[l] / eps - zmax) / den;
+    phi_out[l] = phi < 1.0 ? phi : 1.0;
+  }
+  return DARE_OK;
+}
+
+int dare_policy_mode(int mode, int layer, int step, int skip_layers, int refresh_interval) {
+  if (layer < skip_layers) return DARE_MODE_DENSE;
+  if (refresh_interval > 0 && step % refresh_interval == 0) return DARE_MODE_DENSE;
+  return mode;
+}
+
+dare_status dare_k_quantile_mask(const float* scores, int batch, int seq, float phi, int force_refresh,
+                                 float* tau_out, uint8_t* mask, double* stat_sum, uint64_t* stat_count,
+                                 void* hip_stream) {
+  if (!scores || batch < 1 || seq < 1 || std::isnan(phi) || phi > 1.f) return DARE_ERR_INVALID_ARG;
+  if ((stat_sum == nullptr) != (stat_count == nullptr)) return DARE_ERR_INVALID_ARG;
+  if (phi >= 0.f && !mask) return DARE_ERR_INVALID_ARG;
+  if (phi < 0.f && !stat_sum) return DARE_ERR_INVALID_ARG;
+  const int rank = phi >= 0.f ? (int)ceilf(phi * (float)seq) : -1;
+  hipError_t e = launch_quantile_mask(scores, batch, seq, rank, force_refresh, tau_out, mask, stat_sum,
+                                      reinterpret_cast<unsigned long long*>(stat_count),
+                                      static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }
 

@@ -83,6 +83,9 @@ hipError_t launch_score(const float* q_new, int ld_new, int width, int n_parts, 
 hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_idx,
                           int32_t* sel_idx2, int32_t* sel_count, int32_t* sel_count2,
                           int32_t* sel_off, hipStream_t s);
+hipError_t launch_quantile_mask(const float* scores, int batch, int seq, int rank, int force_refresh,
+                                float* tau_out, uint8_t* mask, double* stat_sum,
+                                unsigned long long* stat_count, hipStream_t s);
 hipError_t launch_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops, hipStream_t s);
 hipError_t launch_copy_rows(const void* src, void* dst, int n_rows, int row_bytes,
                             const int32_t* idx, const int32_t* m_dev, hipStream_t s);

@@ -147,6 +147,119 @@ __global__ void __launch_bounds__(256) compact_kernel(const uint8_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------
+// Threshold from a reuse rate (Sec. 3.1, "Reuse rate allocation"): per sequence, tau is
+// the k-th smallest of its drift scores, found exactly by a radix select over an
+// order-preserving 32-bit key (four passes of 8 bits, most significant first; NaN keys
+// sort last).  One workgroup per sequence; it then writes the reuse decision s <= tau of
+// its tokens and adds the sequence's score sum and count to the running drift statistics
+// (the layer-wise mean drift of the same section).
+//   rank > 0: select and decide; rank = 0: tau = -inf, nothing reused; rank < 0: statistics
+//   only (mask and tau untouched).
+// ---------------------------------------------------------------------------
+__device__ inline unsigned order_key(float s) {
+  if (s != s) return 0xffffffffu;
+  const unsigned u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float key_value(unsigned key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+constexpr int kSelectThreads = 1024;
+
+__global__ void __launch_bounds__(kSelectThreads) quantile_mask_kernel(
+    const float* __restrict__ scores, int seq, int rank, int force_refresh, float* __restrict__ tau_out,
+    uint8_t* __restrict__ mask, double* __restrict__ stat_sum, unsigned long long* __restrict__ stat_count) {
+  __shared__ unsigned hist[256];
+  __shared__ unsigned sh_digit, sh_rank;
+  __shared__ double red_sum[kSelectThreads / 64];
+  __shared__ unsigned red_cnt[kSelectThreads / 64];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* s = scores + (long)b * seq;
+
+  float tau = -INFINITY;
+  if (rank > 0) {
+    unsigned prefix = 0, known = 0, want = (unsigned)rank;  // 1-based rank among the keys that match prefix
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int i = tid; i < seq; i += kSelectThreads) {
+        const unsigned key = order_key(s[i]);
+        if ((key & known) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (wave == 0) {  // lane L owns bins 4L .. 4L+3; find the bin that holds the wanted rank
+        unsigned c[4], tot = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          c[j] = hist[lane * 4 + j];
+          tot += c[j];
+        }
+        unsigned incl = tot;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const unsigned up = __shfl_up(incl, o, 64);
+          if (lane >= o) incl += up;
+        }
+        unsigned before = incl - tot;
+        if (want > before && want <= incl) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (want > before && want <= before + c[j]) {
+              sh_digit = (unsigned)(lane * 4 + j);
+              sh_rank = want - before;
+            }
+            before += c[j];
+          }
+        }
+      }
+      __syncthreads();
+      prefix |= sh_digit << shift;
+      known |= 0xffu << shift;
+      want = sh_rank;
+    }
+    tau = key_value(prefix);
+    if (tau != tau) tau = INFINITY;  // only NaN scores left at this rank: reuse every real score
+  }
+  if (rank >= 0) {
+    if (tid == 0 && tau_out) tau_out[b] = tau;
+    for (int i = tid; i < seq; i += kSelectThreads)
+      mask[(long)b * seq + i] = (!force_refresh && s[i] <= tau) ? 1 : 0;
+  }
+  if (stat_sum) {
+    double sum = 0.0;
+    unsigned cnt = 0;
+    for (int i = tid; i < seq; i += kSelectThreads) {
+      const float v = s[i];
+      if (v == v) {
+        sum += (double)v;
+        ++cnt;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      sum += __shfl_xor(sum, o, 64);
+      cnt += __shfl_xor(cnt, o, 64);
+    }
+    if (lane == 0) {
+      red_sum[wave] = sum;
+      red_cnt[wave] = cnt;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      double t = 0.0;
+      unsigned long long n = 0;
+      for (int w = 0; w < kSelectThreads / 64; ++w) {
+        t += red_sum[w];
+        n += red_cnt[w];
+      }
+      atomicAdd(stat_sum, t);
+      atomicAdd(stat_count, n);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // dst[t] = src[t] for the listed (or all) rows: 16 bytes per lane, a row is a
 // contiguous run of full cache lines.
 // ---------------------------------------------------------------------------
@@ -193,6 +306,15 @@ hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_
   dim3 grid((seq + kChunk - 1) / kChunk, batch);
   hipLaunchKernelGGL(compact_kernel, grid, dim3(256), 0, s, mask, batch, seq, sel_idx, sel_idx2,
                      sel_count, sel_count2, sel_off);
+  return hipGetLastError();
+}
+
+hipError_t launch_quantile_mask(const float* scores, int batch, int seq, int rank, int force_refresh,
+                                float* tau_out, uint8_t* mask, double* stat_sum,
+                                unsigned long long* stat_count, hipStream_t s) {
+  if (batch == 0 || seq == 0) return hipSuccess;
+  hipLaunchKernelGGL(quantile_mask_kernel, dim3(batch), dim3(kSelectThreads), 0, s, scores, seq, rank,
+                     force_refresh, tau_out, mask, stat_sum, stat_count);
   return hipGetLastError();
 }
 

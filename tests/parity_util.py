@@ -104,13 +104,13 @@ def oracle_fill(case):
     }
 
 
-def oracle_step(case, state, mode, tau, x=None, storage="auto"):
+def oracle_step(case, state, mode, tau, x=None, storage="auto", quantile=False):
     x = case["x_cur"] if x is None else x
     if storage == "auto":
         storage = "bf16" if case["dtype"] == "bf16" else None
     return orc.layer_step(mode, tau, x, case["wq"], case["wk"], case["wv"], case["wo"],
                           state["q_prev"], state["k_cache"], state["v_cache"], state["o_cache"],
-                          case["n_heads"], storage=storage)
+                          case["n_heads"], storage=storage, quantile=quantile)
 
 
 def gap_threshold(scores, quantile=0.5, min_gap=8e-6):
@@ -139,7 +139,7 @@ class GpuLayer:
                                  max_batch=max_batch or case["batch"], max_seq=max_seq or case["seq"])
         torch.cuda.synchronize()
 
-    def step(self, mode, tau, x, state, alias_out=True, want_lists=True):
+    def step(self, mode, tau, x, state, alias_out=True, want_lists=True, want_scores=True):
         """Run dare_layer_step on device copies of `state`; returns numpy results."""
         c = self.case
         Bn, T = x.shape[0], x.shape[1]
@@ -149,14 +149,15 @@ class GpuLayer:
         mask = torch.full((Bn, T), 7, dtype=torch.uint8, device="cuda")
         sel_idx = torch.full((Bn * T,), -1, dtype=torch.int32, device="cuda") if want_lists else None
         sel_count = torch.full((Bn,), -1, dtype=torch.int32, device="cuda") if want_lists else None
-        scores = torch.full((Bn, T), float("nan"), dtype=torch.float32, device="cuda")
+        scores = torch.full((Bn, T), float("nan"), dtype=torch.float32, device="cuda") if want_scores else None
         self.layer.layer_step(mode, float(tau), xd, st["q_prev"], st["k_cache"], st["v_cache"],
                               st["o_cache"], out, mask, sel_idx, sel_count, scores)
         torch.cuda.synchronize()
         res = {k: host(v) for k, v in st.items()}
         res["out"] = host(out)
         res["reuse_mask"] = host(mask)
-        res["scores"] = host(scores)
+        if want_scores:
+            res["scores"] = host(scores)
         if want_lists:
             res["sel_idx"] = host(sel_idx)
             res["sel_count"] = host(sel_count)

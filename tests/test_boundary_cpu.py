@@ -96,3 +96,25 @@ def test_kernel_entry_points_reject_bad_arguments(L):
     assert L.dare_k_attention(B.DARE_BF16, f, f, f, f, 1, 8, 2, 64, f, None, None, 0, None) == B.DARE_ERR_INVALID_ARG
     assert L.dare_k_copy_rows(f, f, 4, 24, None, None, None) == B.DARE_ERR_INVALID_ARG
     assert L.dare_k_pack_weight(B.DARE_F32, f, 8, 8, f, 4, None) == B.DARE_ERR_INVALID_ARG
+
+
+def test_allocate_quantiles_host_function_matches_oracle(L):
+    import numpy as np
+    from oracle import dare_oracle as orc
+    s = np.random.Generator(np.random.PCG64(4)).random(32) * 0.3
+    for phi_bar, eps in ((0.3, 0.05), (0.9, 1e-3), (0.5, 10.0)):
+        got = np.array(B.dare_allocate_quantiles(s, phi_bar, eps))
+        assert np.allclose(got, orc.allocate_quantiles(s, phi_bar, eps), rtol=1e-12, atol=1e-15)
+    for bad in ((0.3, 0.0), (1.5, 0.1), (-0.1, 0.1)):
+        with pytest.raises(B.DareError):
+            B.dare_allocate_quantiles(s, *bad)
+
+
+def test_policy_mode_host_function_matches_oracle(L):
+    from oracle import dare_oracle as orc
+    for mode in (1, 2, 3):
+        for layer in (0, 9, 10, 31):
+            for step in range(5):
+                for skip, every in ((0, 0), (10, 0), (0, 2), (10, 3)):
+                    assert B.dare_policy_mode(mode, layer, step, skip, every) == \
+                        orc.policy_mode(mode, layer, step, skip, every)
