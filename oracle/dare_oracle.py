@@ -67,6 +67,15 @@ Readings taken where the paper is silent or has two forms:
     quantile cannot exceed 1; the paper does not say).  ``policy_mode`` is the
     host-side schedule of Sec. 5 (Fast-dLLM-v2 setting): the first layers are not
     reused at all and every r-th step recomputes everything.
+  * frozen prefix (``prefix=P``).  The paper composes DARE with prefix caching (Sec. 1,
+    Sec. 5 "P+C") without defining it; the reading taken is the usual one for
+    diffusion LLMs: the first P tokens of every sequence (the prompt) are frozen: they
+    are never projected, scored or queried, their K, V and output rows stay what the
+    caches hold, and the other tokens attend to them through the K/V caches.  In the
+    terms of this file a frozen token is a token that is always reused, in every mode,
+    DENSE included (there "all rows" means all rows that are not frozen); its score is
+    reported as 0, its mask bit as 1, and its score-cache row is left as it was.  A
+    quantile threshold ranks the scores of the tokens that are not frozen only.
   * precision.  The paper runs in BF16 (Sec. 5, App. A): the tensors its
     algorithms name -- Q, K, V, the attention rows before Wo, the layer output --
     are bf16 tensors, with wide accumulation inside each product.  ``storage=None``
@@ -138,8 +147,9 @@ def reuse_decision(scores, tau):
 
 def quantile_threshold(scores, phi):
     """Sec. 3.1: per sequence, the drift score at the phi-quantile = the k-th smallest
-    of the T scores, k = ceil(phi * T).  scores [B, T]; returns float32 tau [B]
-    (-inf when k = 0; +inf when the k-th smallest is NaN)."""
+    of the T scores, k = ceil(phi * T).  scores [B, T] (pass only the columns that take
+    part in the ranking); returns float32 tau [B] (-inf when k = 0; +inf when the k-th
+    smallest is NaN)."""
     s32 = np.asarray(scores, dtype=np.float64).astype(np.float32)
     B, T = s32.shape
     k = int(np.ceil(np.float32(phi) * np.float32(T)))
@@ -254,7 +264,7 @@ def rope(x, positions, n_heads, base=10000.0):
 
 
 def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
-               n_heads, score_head=0, storage=None, rope_base=None, quantile=False):
+               n_heads, score_head=0, storage=None, rope_base=None, quantile=False, prefix=0):
     """One step of the layer in mode DENSE / KV (Alg. 1) / O (Alg. 2) / KVO.
 
     x [B,T,d]; w* [d,d]; q_prev [B,T,Dh] (or [B,T,d] when score_head = -1);
@@ -263,6 +273,7 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
     projected at this step (see the header).
     quantile: tau is a reuse rate phi in [0, 1]; each sequence's threshold is
     quantile_threshold of its scores (returned as "tau", float32 [B]).
+    prefix: the first `prefix` tokens of every sequence are frozen (see the header).
     Returns a dict with out, k_cache, v_cache, o_cache, q_prev (all updated,
     float64), scores [B,T] float64, reuse_mask uint8 [B,T] (1 = reused),
     sel_idx, sel_count, sel_off, and exact = {out, k_cache, v_cache} before the
@@ -283,15 +294,23 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
     scores = drift_scores(q_sc, _f64(q_prev))
 
     # Alg. 1/2 lines 4-5.
+    if not 0 <= prefix < T:
+        raise ValueError("prefix must lie in [0, seq)")
+    frozen = np.zeros((B, T), dtype=bool)
+    frozen[:, :prefix] = True
+    scores[frozen] = 0.0
     if quantile:
-        tau_b = quantile_threshold(scores, tau)
+        tau_b = quantile_threshold(scores[:, prefix:], tau)
     else:
         tau_b = np.full(B, np.float32(tau), dtype=np.float32)
     if mode == MODE_DENSE:
         reuse = np.zeros((B, T), dtype=bool)
     else:
         reuse = np.stack([reuse_decision(scores[b], tau_b[b]) for b in range(B)])
+    reuse |= frozen
     sel_idx, sel_count, sel_off = selection(reuse)
+    # rows the "all rows" steps of a mode run over: every token that is not frozen
+    active = ~frozen
     # rotary embedding of queries and of the keys projected at this step (position =
     # index in the sequence); the score above used the unrotated query
     pos = np.arange(T, dtype=np.float64)
@@ -308,10 +327,17 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
             rows = np.flatnonzero(~reuse[b])
             K_exact[b, rows] = rot(x[b, rows] @ wk, rows)
             V_exact[b, rows] = x[b, rows] @ wv
-    else:
+    elif prefix == 0:
         # Alg. 2 line 7 / App. E.2.
         K_exact = rot(x @ wk)
         V_exact = x @ wv
+    else:
+        # the same for the rows that are not frozen; frozen rows keep the cache
+        K_exact = _f64(k_cache).copy()
+        V_exact = _f64(v_cache).copy()
+        rows = np.arange(prefix, T)
+        K_exact[:, rows] = rot(x[:, rows] @ wk, rows)
+        V_exact[:, rows] = x[:, rows] @ wv
     K = round_storage(K_exact, storage)
     V = round_storage(V_exact, storage)
 
@@ -324,11 +350,12 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
             attn = round_storage(attention_rows(Qs[b, rows], K[b], V[b], n_heads), storage)
             out_exact[b, rows] = attn @ wo
     else:
-        # Alg. 1 lines 10-11.
-        out_exact = np.empty((B, T, d), dtype=np.float64)
+        # Alg. 1 lines 10-11 (frozen rows return the cached output).
+        out_exact = _f64(o_cache).copy()
         for b in range(B):
-            attn = round_storage(attention_rows(Qs[b], K[b], V[b], n_heads), storage)
-            out_exact[b] = attn @ wo
+            rows = np.flatnonzero(active[b])
+            attn = round_storage(attention_rows(Qs[b, rows], K[b], V[b], n_heads), storage)
+            out_exact[b, rows] = attn @ wo
     out = round_storage(out_exact, storage)
 
     return {
@@ -337,7 +364,7 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
         "v_cache": V,
         "o_cache": out.copy(),
         "exact": {"out": out_exact, "k_cache": K_exact, "v_cache": V_exact},
-        "q_prev": q_sc.copy(),
+        "q_prev": np.where(frozen[:, :, None], _f64(q_prev), q_sc),
         "scores": scores,
         "tau": tau_b,
         "reuse_mask": reuse.astype(np.uint8),
@@ -349,7 +376,7 @@ def layer_step(mode, tau, x, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
 
 def block_step(mode, tau, x, norm, gain, bias, eps, wq, wk, wv, wo, q_prev, k_cache,
                v_cache, o_cache, n_heads, score_head=0, storage=None, rope_base=None,
-               residual=True, quantile=False):
+               residual=True, quantile=False, prefix=0):
     """The attention block around ``layer_step``: h = norm(x) (Alg. 1/2 line 1; norm is
     "layer", "rms" or None), the layer step on h, then out = x + O when residual.
 
@@ -368,7 +395,7 @@ def block_step(mode, tau, x, norm, gain, bias, eps, wq, wk, wv, wo, q_prev, k_ca
     h = round_storage(h, storage)          # the normalised hidden state is a stored tensor
     r = layer_step(mode, tau, h, wq, wk, wv, wo, q_prev, k_cache, v_cache, o_cache,
                    n_heads, score_head=score_head, storage=storage, rope_base=rope_base,
-                   quantile=quantile)
+                   quantile=quantile, prefix=prefix)
     r["h"] = h
     exact_block = x + r["out"] if residual else r["out"].copy()
     r["exact"]["block_out"] = exact_block

@@ -110,3 +110,93 @@ def test_policy_mode_schedule():
     assert [orc.policy_mode(M, 12, t, refresh_interval=2) for t in range(5)] == [0, M, 0, M, 0]
     assert [orc.policy_mode(M, 12, t) for t in range(3)] == [M, M, M]
     assert orc.policy_mode(orc.MODE_O, 3, 1, skip_layers=10, refresh_interval=2) == orc.MODE_DENSE
+
+
+# ---- frozen prefix (prefix caching) ---------------------------------------------------------
+
+def _prefix_case(seed=11, B=2, T=24, d=16, H=2, P=9):
+    r = _rng(seed)
+    w = [r.standard_normal((d, d)) * 0.3 for _ in range(4)]
+    x_prev = r.standard_normal((B, T, d))
+    x = x_prev + 0.4 * r.standard_normal((B, T, d))
+    out, Q, K, V = orc.dense_layer(x_prev, *w, H)
+    state = (Q[:, :, :d // H].copy(), K, V, out)
+    return w, x, state, H, P
+
+
+def _loops_attention_row(q, K, V, H):
+    """One query row against all keys, scalar loops (second formulation of App. E.2)."""
+    d = len(q)
+    dh = d // H
+    o = np.zeros(d)
+    for h in range(H):
+        z = [sum(q[h * dh + c] * K[j][h * dh + c] for c in range(dh)) / np.sqrt(dh) for j in range(len(K))]
+        m = max(z)
+        wgt = [np.exp(v - m) for v in z]
+        for c in range(dh):
+            o[h * dh + c] = sum(wgt[j] * V[j][h * dh + c] for j in range(len(K))) / sum(wgt)
+    return o
+
+
+@pytest.mark.parametrize("mode", [orc.MODE_DENSE, orc.MODE_KV, orc.MODE_O, orc.MODE_KVO])
+def test_frozen_prefix_rows_are_untouched_and_never_scored(mode):
+    w, x, (qp, K, V, O), H, P = _prefix_case()
+    r = orc.layer_step(mode, 0.05, x, *w, qp, K, V, O, H, prefix=P)
+    assert r["reuse_mask"][:, :P].all() and (r["scores"][:, :P] == 0).all()
+    assert np.array_equal(r["q_prev"][:, :P], qp[:, :P])
+    assert np.array_equal(r["k_cache"][:, :P], K[:, :P]) and np.array_equal(r["v_cache"][:, :P], V[:, :P])
+    assert np.array_equal(r["out"][:, :P], O[:, :P])
+    assert (r["sel_idx"] % x.shape[1] >= P).all()
+    if mode == orc.MODE_DENSE:
+        assert (r["reuse_mask"][:, P:] == 0).all()
+        assert r["sel_count"].tolist() == [x.shape[1] - P] * x.shape[0]
+
+
+@pytest.mark.parametrize("mode", [orc.MODE_DENSE, orc.MODE_KV, orc.MODE_O, orc.MODE_KVO])
+def test_frozen_prefix_active_rows_by_scalar_loops(mode):
+    # the rows that are not frozen, recomputed with scalar loops from the K/V the step must see
+    w, x, (qp, K, V, O), H, P = _prefix_case(B=1, T=10, d=8, P=4)
+    wq, wk, wv, wo = w
+    tau = 0.05
+    r = orc.layer_step(mode, tau, x, *w, qp, K, V, O, H, prefix=P)
+    T = x.shape[1]
+    refreshed = [i for i in range(P, T) if mode == orc.MODE_DENSE or r["scores"][0, i] > np.float32(tau)]
+    kv_rows = refreshed if mode in (orc.MODE_KV, orc.MODE_KVO) else list(range(P, T))
+    Kx, Vx = K[0].copy(), V[0].copy()
+    for i in kv_rows:
+        Kx[i], Vx[i] = x[0, i] @ wk, x[0, i] @ wv
+    assert np.allclose(r["k_cache"][0], Kx, atol=1e-12) and np.allclose(r["v_cache"][0], Vx, atol=1e-12)
+    q_rows = refreshed if mode in (orc.MODE_O, orc.MODE_KVO) else list(range(P, T))
+    for i in range(T):
+        want = _loops_attention_row(x[0, i] @ wq, Kx, Vx, H) @ wo if i in q_rows else O[0, i]
+        assert np.allclose(r["out"][0, i], want, atol=1e-10), i
+
+
+def test_frozen_prefix_equals_forcing_a_zero_score():
+    # without the prefix argument: give the frozen tokens a previous query equal to the current
+    # one, so that they score exactly 0 and tau = 0 reuses them; the refreshed rows must agree
+    w, x, (qp, K, V, O), H, P = _prefix_case()
+    q_now = (x @ w[0])[:, :, :qp.shape[2]]
+    qp2 = qp.copy()
+    qp2[:, :P] = q_now[:, :P]
+    a = orc.layer_step(orc.MODE_KVO, 0.0, x, *w, qp2, K, V, O, H)
+    b = orc.layer_step(orc.MODE_KVO, 0.0, x, *w, qp, K, V, O, H, prefix=P)
+    assert np.array_equal(a["reuse_mask"], b["reuse_mask"]) and np.array_equal(a["sel_idx"], b["sel_idx"])
+    for k in ("out", "k_cache", "v_cache"):
+        assert np.allclose(a[k], b[k], atol=1e-12), k
+
+
+def test_frozen_prefix_quantile_ranks_only_the_other_tokens():
+    w, x, (qp, K, V, O), H, P = _prefix_case(T=29, P=9)
+    r = orc.layer_step(orc.MODE_KVO, 0.5, x, *w, qp, K, V, O, H, quantile=True, prefix=P)
+    assert (r["reuse_mask"][:, P:].sum(axis=1) == 10).all()           # ceil(0.5 * 20) of the 20 others
+    assert np.array_equal(r["tau"], np.sort(r["scores"][:, P:].astype(np.float32), axis=1)[:, 9])
+
+
+def test_frozen_prefix_of_zero_is_the_plain_step_and_bad_values_raise():
+    w, x, (qp, K, V, O), H, P = _prefix_case()
+    a = orc.layer_step(orc.MODE_KV, 0.05, x, *w, qp, K, V, O, H)
+    b = orc.layer_step(orc.MODE_KV, 0.05, x, *w, qp, K, V, O, H, prefix=0)
+    assert all(np.array_equal(a[k], b[k]) for k in ("out", "k_cache", "reuse_mask", "q_prev"))
+    with pytest.raises(ValueError):
+        orc.layer_step(orc.MODE_KV, 0.05, x, *w, qp, K, V, O, H, prefix=x.shape[1])
