@@ -213,6 +213,19 @@ dare_status dare_allocate_quantiles(int n_layers, const double* s, double phi_ba
  */
 int dare_policy_mode(int mode, int layer, int step, int skip_layers, int refresh_interval);
 
+/*
+ * Frozen prefix (prefix caching composed with the reuse modes; Sec. 1 and Sec. 5 name the
+ * combination, the reading is the common one for diffusion LLMs): the first prefix_len
+ * tokens of every sequence are never projected, scored or queried by the step calls
+ * that follow.  Their K, V and output cache rows are read as they are (the caller
+ * filled them with an earlier step at prefix_len = 0), their reuse_mask byte is 1, their
+ * score 0, their q_prev row is left alone, and `out` returns their cached row.  In every
+ * mode, DENSE included, "all rows" then means all rows that are not frozen; a quantile
+ * threshold ranks the other tokens only.  prefix_len = 0 switches it off.
+ * INVALID_ARG: prefix_len < 0 or >= max_seq; a later step with seq <= prefix_len.
+ */
+dare_status dare_set_prefix(dare_ctx* ctx, int prefix_len);
+
 /* Free a context and its device memory.  NULL is a no-op. */
 dare_status dare_destroy(dare_ctx* ctx);
 

@@ -24,7 +24,7 @@ EXPORTS = (
     "dare_block_attach", "dare_block_step", "dare_k_gemm_rope", "dare_k_rope_table",
     "dare_k_norm", "dare_k_residual_add",
     "dare_set_threshold_rule", "dare_get_thresholds", "dare_drift_stats_enable", "dare_drift_stats_read",
-    "dare_allocate_quantiles", "dare_policy_mode", "dare_k_quantile_mask",
+    "dare_allocate_quantiles", "dare_policy_mode", "dare_k_quantile_mask", "dare_set_prefix",
 )
 RULE_SCORE, RULE_QUANTILE = 0, 1
 NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2
@@ -125,6 +125,8 @@ def lib():
     L.dare_allocate_quantiles.restype = i32
     L.dare_policy_mode.argtypes = [i32] * 5
     L.dare_policy_mode.restype = i32
+    L.dare_set_prefix.argtypes = [vp, i32]
+    L.dare_set_prefix.restype = i32
     L.dare_k_quantile_mask.argtypes = [vp, i32, i32, f32, i32, vp, vp, vp, vp, vp]
     L.dare_k_quantile_mask.restype = i32
     _lib = L
@@ -218,6 +220,9 @@ class DareLayer:
                                    _ptr(reuse_mask), _ptr(sel_idx), _ptr(sel_count), _ptr(scores),
                                    _stream(stream))
         _check(st, self._ctx)
+
+    def set_prefix(self, prefix_len):
+        _check(lib().dare_set_prefix(self._ctx, prefix_len), self._ctx)
 
     def set_threshold_rule(self, rule):
         _check(lib().dare_set_threshold_rule(self._ctx, rule), self._ctx)

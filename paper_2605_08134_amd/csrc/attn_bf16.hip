@@ -358,7 +358,7 @@ hipError_t launch_dh(const AttnDev& p, const AttnArgs& a, int cfg, hipStream_t s
   // key-waves).  Refreshed rows are few per sequence: with few (sequence, head) pairs
   // the narrow block (64 rows, 4 key-waves) is what fills the chip; with many pairs
   // the wide block already does and re-reads K and V less.
-  if (a.idx && a.batch * a.n_heads < 128) return launch_variant<DH, 2, 4, 32, 2>(p, a, s);
+  if (a.idx && !a.many_rows && a.batch * a.n_heads < 128) return launch_variant<DH, 2, 4, 32, 2>(p, a, s);
   return launch_variant<DH, 4, 2, 64, 2>(p, a, s);
 }
 

@@ -39,6 +39,11 @@ struct dare_ctx {
   float* tau_dev;      // [max_batch] thresholds of the last quantile step
   float* scores_buf;   // [max tokens] scores when the caller passes none
   double* stat_sum;    // one fp64 sum followed by one 64-bit count
+  // frozen prefix
+  int prefix;          // tokens [0, prefix) of every sequence are frozen
+  int32_t* act_idx;    // [max tokens] ids of the tokens that are not frozen
+  int32_t* act_off;    // [max_batch + 1] offsets of the sequences in act_idx
+  int act_batch, act_seq, act_prefix;  // what act_idx / act_off currently describe
   std::string err;
 };
 
@@ -84,7 +89,7 @@ void free_ctx(dare_ctx* c) {
   if (!c) return;
   void* bufs[] = {c->wqkv_t, c->wo_t, c->q_buf, c->attn_buf, c->q_new, c->sel_idx, c->sel_off,
                   c->attn_work, c->gain, c->bias, c->h_buf, c->rope_table, c->tau_dev, c->scores_buf,
-                  c->stat_sum};
+                  c->stat_sum, c->act_idx, c->act_off};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   delete c;
@@ -149,6 +154,9 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, 
   c->stats_on = false;
   c->tau_dev = c->scores_buf = nullptr;
   c->stat_sum = nullptr;
+  c->prefix = 0;
+  c->act_idx = c->act_off = nullptr;
+  c->act_batch = c->act_seq = c->act_prefix = -1;
   const size_t d = cfg->hidden;
   c->attn_work_bytes = cfg->dtype == DARE_BF16
                            ? attn_bf16_work_bytes(cfg->max_batch, cfg->max_seq, cfg->n_heads, cfg->head_dim)
@@ -216,6 +224,7 @@ dare_status check_step_args(dare_ctx* ctx, int mode, float threshold, int batch,
   if (std::isnan(threshold)) return fail(ctx, DARE_ERR_INVALID_ARG, "threshold is NaN");
   if (ctx->rule == DARE_RULE_QUANTILE && !(threshold >= 0.f && threshold <= 1.f))
     return fail(ctx, DARE_ERR_INVALID_ARG, "under the quantile rule the threshold is a reuse rate in [0, 1]");
+  if (ctx->prefix >= seq) return fail(ctx, DARE_ERR_INVALID_ARG, "the frozen prefix covers the whole sequence");
   return DARE_OK;
 }
 
@@ -237,13 +246,28 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
   hipError_t e;
   int k_parts = 1;
 
+  // Frozen prefix: "all rows" below means the rows of this list, and their results go into
+  // the caches at their token index as the refreshed rows' do.
+  const int P = ctx->prefix;
+  const bool pre = P > 0;
+  const int n_act = batch * (seq - P);
+  if (pre && (ctx->act_batch != batch || ctx->act_seq != seq || ctx->act_prefix != P)) {
+    if ((e = launch_active_list(batch, seq, P, ctx->act_idx, ctx->act_off, s)) != hipSuccess)
+      return fail_hip(ctx, e, "active-row list");
+    ctx->act_batch = batch;
+    ctx->act_seq = seq;
+    ctx->act_prefix = P;
+  }
+  const int32_t* act_idx = pre ? ctx->act_idx : nullptr;
+
   // 1. Query projection feeding the score (Alg. 1/2 line 2), together with whatever
   //    else this mode projects for all rows.
   GemmArgs g{};
   g.a = hidden;
   g.lda = d;
   g.k = d;
-  g.m_max = n_tok;
+  g.m_max = n_act;
+  g.idx = act_idx;
   g.ldc = d;
   g.seg_n = d;
   g.c32 = ctx->q_new;
@@ -267,7 +291,7 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
     g.n = sw;  // only the scored columns of Q for every row
     // few output tiles, long k: cut k into ranges that the score kernel adds up
     if (cf.dtype == DARE_BF16) {
-      const int tiles = ((n_tok + 63) / 64) * ((sw + 63) / 64), ksteps = d / 64;
+      const int tiles = ((n_act + 63) / 64) * ((sw + 63) / 64), ksteps = d / 64;
       while (tiles * k_parts * 2 <= 256 && k_parts * 2 <= 8 && ksteps % (k_parts * 2) == 0 &&
              ksteps / (k_parts * 2) >= 4 && (size_t)n_tok * sw * (k_parts * 2) <= ctx->q_new_elems)
         k_parts *= 2;
@@ -284,13 +308,13 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
   float* sc = scores;
   if (!sc && (by_rate || ctx->stats_on)) sc = ctx->scores_buf;
   e = launch_score(ctx->q_new, sw, sw, k_parts, (long)n_tok * sw, q_prev, n_tok, by_rate ? 0.f : threshold,
-                   mode == DARE_MODE_DENSE || by_rate, sc, nullptr, reuse_mask, s);
+                   mode == DARE_MODE_DENSE || by_rate, sc, nullptr, reuse_mask, seq, P, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "score");
   if (by_rate || ctx->stats_on) {
-    const int rank = by_rate ? (int)ceilf(threshold * (float)seq) : -1;
+    const int rank = by_rate ? (int)ceilf(threshold * (float)(seq - P)) : -1;
     double* sum = ctx->stats_on ? ctx->stat_sum : nullptr;
-    e = launch_quantile_mask(sc, batch, seq, rank, mode == DARE_MODE_DENSE, ctx->tau_dev, reuse_mask, sum,
-                             reinterpret_cast<unsigned long long*>(sum ? sum + 1 : nullptr), s);
+    e = launch_quantile_mask(sc, batch, seq, P, seq - P, rank, mode == DARE_MODE_DENSE, ctx->tau_dev, reuse_mask,
+                             sum, reinterpret_cast<unsigned long long*>(sum ? sum + 1 : nullptr), s);
     if (e != hipSuccess) return fail_hip(ctx, e, "threshold selection");
   }
 
@@ -343,8 +367,9 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
   a.seq = seq;
   a.n_heads = cf.n_heads;
   a.head_dim = cf.head_dim;
-  a.idx = sel_o ? ctx->sel_idx : nullptr;
-  a.sel_off = sel_o ? ctx->sel_off : nullptr;
+  a.idx = sel_o ? ctx->sel_idx : act_idx;
+  a.sel_off = sel_o ? ctx->sel_off : (pre ? ctx->act_off : nullptr);
+  a.many_rows = !sel_o && pre;
   a.work = ctx->attn_work;
   a.work_bytes = ctx->attn_work_bytes;
   if ((e = attn(ctx, a, s)) != hipSuccess) return fail_hip(ctx, e, "attention");
@@ -363,6 +388,10 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
     o.idx = ctx->sel_idx;
     o.m_dev = n_sel;
     o.c[0] = o_cache;
+  } else if (pre) {
+    o.idx = act_idx;
+    o.m_max = n_act;
+    o.c[0] = o_cache;
   } else {
     o.c[0] = bx.x_resid ? o_cache : out;
   }
@@ -374,8 +403,8 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
     e = launch_residual_add(cf.dtype, bx.x_resid, o_cache, out, (long)n_tok * d, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "residual sum");
   } else if (out != o_cache) {
-    e = sel_o ? launch_copy_rows(o_cache, out, n_tok, (int)(d * es), nullptr, nullptr, s)
-              : launch_copy_rows(out, o_cache, n_tok, (int)(d * es), nullptr, nullptr, s);
+    e = (sel_o || pre) ? launch_copy_rows(o_cache, out, n_tok, (int)(d * es), nullptr, nullptr, s)
+                       : launch_copy_rows(out, o_cache, n_tok, (int)(d * es), nullptr, nullptr, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "output copy");
   }
   return DARE_OK;
@@ -479,8 +508,9 @@ dare_status dare_block_step(dare_ctx* ctx, int mode, float threshold, int batch,
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const void* hidden = x;
   if (bc.norm != DARE_NORM_NONE) {  // Alg. 1/2 line 1
+    const int P = ctx->prefix;  // frozen rows are not normalised: nothing reads them
     hipError_t e = launch_norm(ctx->cfg.dtype, bc.norm, x, ctx->gain, ctx->has_bias ? ctx->bias : nullptr,
-                               bc.eps, batch * seq, ctx->cfg.hidden, ctx->h_buf, s);
+                               bc.eps, batch * (seq - P), ctx->cfg.hidden, ctx->h_buf, P > 0 ? seq : 0, P, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "normalisation");
     hidden = ctx->h_buf;
   }
@@ -569,6 +599,30 @@ dare_status dare_set_threshold_rule(dare_ctx* ctx, int rule) {
   return DARE_OK;
 }
 
+dare_status dare_set_prefix(dare_ctx* ctx, int prefix_len) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (prefix_len < 0 || prefix_len >= ctx->cfg.max_seq)
+    return fail(ctx, DARE_ERR_INVALID_ARG, "prefix_len must lie in [0, max_seq)");
+  if (prefix_len > 0 && !ctx->act_idx) {
+    DeviceGuard guard;
+    hipError_t e = guard.enter(ctx->cfg.device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    const size_t max_tok = (size_t)ctx->cfg.max_batch * ctx->cfg.max_seq;
+    if ((e = hipMalloc((void**)&ctx->act_idx, max_tok * sizeof(int32_t))) != hipSuccess) {
+      ctx->act_idx = nullptr;
+      return fail_hip(ctx, e, "hipMalloc");
+    }
+    if ((e = hipMalloc((void**)&ctx->act_off, ((size_t)ctx->cfg.max_batch + 1) * sizeof(int32_t))) != hipSuccess) {
+      ctx->act_off = nullptr;
+      (void)hipFree(ctx->act_idx);
+      ctx->act_idx = nullptr;
+      return fail_hip(ctx, e, "hipMalloc");
+    }
+  }
+  ctx->prefix = prefix_len;
+  return DARE_OK;
+}
+
 dare_status dare_get_thresholds(dare_ctx* ctx, float* dst, int batch, void* hip_stream) {
   if (!ctx) return DARE_ERR_INVALID_ARG;
   if (!dst || batch < 1 || batch > ctx->cfg.max_batch) return fail(ctx, DARE_ERR_INVALID_ARG, "bad dst or batch");
@@ -647,7 +701,7 @@ dare_status dare_k_quantile_mask(const float* scores, int batch, int seq, float 
   if (phi >= 0.f && !mask) return DARE_ERR_INVALID_ARG;
   if (phi < 0.f && !stat_sum) return DARE_ERR_INVALID_ARG;
   const int rank = phi >= 0.f ? (int)ceilf(phi * (float)seq) : -1;
-  hipError_t e = launch_quantile_mask(scores, batch, seq, rank, force_refresh, tau_out, mask, stat_sum,
+  hipError_t e = launch_quantile_mask(scores, batch, seq, 0, seq, rank, force_refresh, tau_out, mask, stat_sum,
                                       reinterpret_cast<unsigned long long*>(stat_count),
                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
@@ -706,7 +760,7 @@ dare_status dare_k_norm(int dtype, int kind, const void* x, const void* gain, co
   if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
   if (kind != DARE_NORM_LAYER && kind != DARE_NORM_RMS) return DARE_ERR_INVALID_ARG;
   if (kind == DARE_NORM_RMS && bias) return DARE_ERR_INVALID_ARG;
-  hipError_t e = launch_norm(dtype, kind, x, gain, bias, eps, n_rows, d, out, static_cast<hipStream_t>(hip_stream));
+  hipError_t e = launch_norm(dtype, kind, x, gain, bias, eps, n_rows, d, out, 0, 0, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }
 
@@ -726,7 +780,7 @@ dare_status dare_k_score(const float* q_new, int ld_new, int width, int n_parts,
   if (n_parts < 1 || (n_parts > 1 && part_stride < (long)n_tokens * ld_new)) return DARE_ERR_INVALID_ARG;
   hipError_t e = launch_score(q_new, ld_new, width, n_parts, part_stride, q_prev, n_tokens, threshold,
                               force_refresh, scores,
-                              nullptr, mask, static_cast<hipStream_t>(hip_stream));
+                              nullptr, mask, 1, 0, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }
 

@@ -68,6 +68,7 @@ struct AttnArgs {
   int batch, seq, n_heads, head_dim;
   const int32_t* idx;      // optional selected rows
   const int32_t* sel_off;  // [batch+1] when idx != nullptr
+  bool many_rows;          // the listed rows are most of each sequence (a frozen prefix), not a few
   void* work;
   uint64_t work_bytes;
 };
@@ -79,18 +80,20 @@ hipError_t launch_pack_weight(int dtype, const void* w, int rows_k, int cols_n, 
                               int ldwt, hipStream_t s);
 hipError_t launch_score(const float* q_new, int ld_new, int width, int n_parts, long part_stride,
                         float* q_prev, int n_tokens, float threshold, int force_refresh, float* scores, float* scores2,
-                        uint8_t* mask, hipStream_t s);
+                        uint8_t* mask, int seq, int prefix, hipStream_t s);
 hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_idx,
                           int32_t* sel_idx2, int32_t* sel_count, int32_t* sel_count2,
                           int32_t* sel_off, hipStream_t s);
-hipError_t launch_quantile_mask(const float* scores, int batch, int seq, int rank, int force_refresh,
-                                float* tau_out, uint8_t* mask, double* stat_sum,
+hipError_t launch_quantile_mask(const float* scores, int batch, int stride, int first, int seq, int rank,
+                                int force_refresh, float* tau_out, uint8_t* mask, double* stat_sum,
                                 unsigned long long* stat_count, hipStream_t s);
+hipError_t launch_active_list(int batch, int seq, int prefix, int32_t* act_idx, int32_t* act_off, hipStream_t s);
 hipError_t launch_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops, hipStream_t s);
 hipError_t launch_copy_rows(const void* src, void* dst, int n_rows, int row_bytes,
                             const int32_t* idx, const int32_t* m_dev, hipStream_t s);
+// rows r = 0 .. n_rows-1; with seq > 0 row r is token (r / (seq - prefix)) * seq + prefix + r % (seq - prefix)
 hipError_t launch_norm(int dtype, int kind, const void* x, const void* gain, const void* bias, float eps,
-                       int n_rows, int d, void* out, hipStream_t s);
+                       int n_rows, int d, void* out, int seq, int prefix, hipStream_t s);
 hipError_t launch_residual_add(int dtype, const void* x, const void* o, void* out, long n_elems,
                                hipStream_t s);
 

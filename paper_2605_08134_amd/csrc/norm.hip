@@ -53,10 +53,12 @@ constexpr int kHold = 4;
 template <typename T>
 __global__ void __launch_bounds__(256) norm_kernel(const T* __restrict__ x, const T* __restrict__ gain,
                                                    const T* __restrict__ bias, float eps, int d, int kind,
-                                                   T* __restrict__ out) {
+                                                   T* __restrict__ out, int seq, int prefix) {
   __shared__ float sh[4];
-  const T* row = x + (long)blockIdx.x * d;
-  T* orow = out + (long)blockIdx.x * d;
+  long tok = blockIdx.x;
+  if (seq > 0) tok = (tok / (seq - prefix)) * seq + prefix + tok % (seq - prefix);  // skip a frozen prefix
+  const T* row = x + tok * d;
+  T* orow = out + tok * d;
   const int groups = d >> 3;
   float v[kHold][8];
   float s1 = 0.f;
@@ -141,16 +143,16 @@ __global__ void __launch_bounds__(256) residual_add_kernel(const T* __restrict__
 }  // namespace
 
 hipError_t launch_norm(int dtype, int kind, const void* x, const void* gain, const void* bias, float eps,
-                       int n_rows, int d, void* out, hipStream_t s) {
+                       int n_rows, int d, void* out, int seq, int prefix, hipStream_t s) {
   if (n_rows == 0) return hipSuccess;
   if (dtype == DARE_BF16)
     hipLaunchKernelGGL(norm_kernel<bf16_t>, dim3(n_rows), dim3(256), 0, s, static_cast<const bf16_t*>(x),
                        static_cast<const bf16_t*>(gain), static_cast<const bf16_t*>(bias), eps, d, kind,
-                       static_cast<bf16_t*>(out));
+                       static_cast<bf16_t*>(out), seq, prefix);
   else
     hipLaunchKernelGGL(norm_kernel<float>, dim3(n_rows), dim3(256), 0, s, static_cast<const float*>(x),
                        static_cast<const float*>(gain), static_cast<const float*>(bias), eps, d, kind,
-                       static_cast<float*>(out));
+                       static_cast<float*>(out), seq, prefix);
   return hipGetLastError();
 }
 

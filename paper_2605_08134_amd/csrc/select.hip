@@ -45,10 +45,18 @@ __global__ void __launch_bounds__(256) score_kernel(const float* __restrict__ q_
                                                    int n_tokens, float threshold,
                                                    int force_refresh, float* __restrict__ scores,
                                                    float* __restrict__ scores2,
-                                                   uint8_t* __restrict__ mask) {
+                                                   uint8_t* __restrict__ mask, int seq, int prefix) {
   const int lane = threadIdx.x & 63;
   const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tok >= n_tokens) return;
+  if (prefix > 0 && tok % seq < prefix) {  // frozen token: always reused, never scored
+    if (lane == 0) {
+      if (scores) scores[tok] = 0.f;
+      if (scores2) scores2[tok] = 0.f;
+      mask[tok] = 1;
+    }
+    return;
+  }
   const float* q = q_new + (long)tok * ld_new;
   float* p = q_prev + (long)tok * width;
   float dot = 0.f, nq = 0.f, np = 0.f;
@@ -168,14 +176,17 @@ __device__ inline float key_value(unsigned key) {
 constexpr int kSelectThreads = 1024;
 
 __global__ void __launch_bounds__(kSelectThreads) quantile_mask_kernel(
-    const float* __restrict__ scores, int seq, int rank, int force_refresh, float* __restrict__ tau_out,
-    uint8_t* __restrict__ mask, double* __restrict__ stat_sum, unsigned long long* __restrict__ stat_count) {
+    const float* __restrict__ scores, int stride, int first, int seq, int rank, int force_refresh,
+    float* __restrict__ tau_out, uint8_t* __restrict__ mask, double* __restrict__ stat_sum,
+    unsigned long long* __restrict__ stat_count) {
   __shared__ unsigned hist[256];
   __shared__ unsigned sh_digit, sh_rank;
   __shared__ double red_sum[kSelectThreads / 64];
   __shared__ unsigned red_cnt[kSelectThreads / 64];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* s = scores + (long)b * seq;
+  // tokens [first, first + seq) of a sequence of `stride` tokens take part
+  const float* s = scores + (long)b * stride + first;
+  mask += (long)b * stride + first;
 
   float tau = -INFINITY;
   if (rank > 0) {
@@ -224,7 +235,7 @@ __global__ void __launch_bounds__(kSelectThreads) quantile_mask_kernel(
   if (rank >= 0) {
     if (tid == 0 && tau_out) tau_out[b] = tau;
     for (int i = tid; i < seq; i += kSelectThreads)
-      mask[(long)b * seq + i] = (!force_refresh && s[i] <= tau) ? 1 : 0;
+      mask[i] = (!force_refresh && s[i] <= tau) ? 1 : 0;
   }
   if (stat_sum) {
     double sum = 0.0;
@@ -257,6 +268,20 @@ __global__ void __launch_bounds__(kSelectThreads) quantile_mask_kernel(
       atomicAdd(stat_count, n);
     }
   }
+}
+
+// ---------------------------------------------------------------------------
+// Row list of the tokens that are not frozen: ids b*seq + prefix .. b*seq + seq - 1 of
+// every sequence, ascending, and the offsets b * (seq - prefix) of the sequences in it.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) active_list_kernel(int batch, int seq, int prefix, int32_t* __restrict__ act_idx,
+                                                         int32_t* __restrict__ act_off) {
+  const int ta = seq - prefix;
+  const long n = (long)batch * ta;
+  for (long r = (long)blockIdx.x * 256 + threadIdx.x; r < n; r += (long)gridDim.x * 256)
+    act_idx[r] = (int32_t)((r / ta) * seq + prefix + r % ta);
+  if (blockIdx.x == 0)
+    for (int b = threadIdx.x; b <= batch; b += 256) act_off[b] = b * ta;
 }
 
 // ---------------------------------------------------------------------------
@@ -293,10 +318,11 @@ hipError_t launch_pack_weight(int dtype, const void* w, int rows_k, int cols_n, 
 
 hipError_t launch_score(const float* q_new, int ld_new, int width, int n_parts, long part_stride,
                         float* q_prev, int n_tokens, float threshold, int force_refresh, float* scores, float* scores2,
-                        uint8_t* mask, hipStream_t s) {
+                        uint8_t* mask, int seq, int prefix, hipStream_t s) {
   if (n_tokens == 0) return hipSuccess;
   hipLaunchKernelGGL(score_kernel, dim3((n_tokens + 3) / 4), dim3(256), 0, s, q_new, ld_new, width,
-                     n_parts, part_stride, q_prev, n_tokens, threshold, force_refresh, scores, scores2, mask);
+                     n_parts, part_stride, q_prev, n_tokens, threshold, force_refresh, scores, scores2, mask,
+                     seq, prefix);
   return hipGetLastError();
 }
 
@@ -309,12 +335,20 @@ hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_
   return hipGetLastError();
 }
 
-hipError_t launch_quantile_mask(const float* scores, int batch, int seq, int rank, int force_refresh,
-                                float* tau_out, uint8_t* mask, double* stat_sum,
+hipError_t launch_quantile_mask(const float* scores, int batch, int stride, int first, int seq, int rank,
+                                int force_refresh, float* tau_out, uint8_t* mask, double* stat_sum,
                                 unsigned long long* stat_count, hipStream_t s) {
   if (batch == 0 || seq == 0) return hipSuccess;
-  hipLaunchKernelGGL(quantile_mask_kernel, dim3(batch), dim3(kSelectThreads), 0, s, scores, seq, rank,
-                     force_refresh, tau_out, mask, stat_sum, stat_count);
+  hipLaunchKernelGGL(quantile_mask_kernel, dim3(batch), dim3(kSelectThreads), 0, s, scores, stride, first, seq,
+                     rank, force_refresh, tau_out, mask, stat_sum, stat_count);
+  return hipGetLastError();
+}
+
+hipError_t launch_active_list(int batch, int seq, int prefix, int32_t* act_idx, int32_t* act_off, hipStream_t s) {
+  const long n = (long)batch * (seq - prefix);
+  const int grid = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  hipLaunchKernelGGL(active_list_kernel, dim3(grid < 1 ? 1 : grid), dim3(256), 0, s, batch, seq, prefix, act_idx,
+                     act_off);
   return hipGetLastError();
 }
 
