@@ -155,7 +155,8 @@ dare_status dare_block_attach(dare_ctx* ctx, const dare_block_config* cfg,
  * out = x + O (residual = 1) or O.  Arguments as dare_layer_step, except:
  *   x        in      [batch, seq, hidden] dtype: the hidden state BEFORE normalisation
  *   o_cache  in/out  the block output O before the residual sum
- *   out      out     with residual = 1 it must not be o_cache (INVALID_ARG)
+ *   out      out     with residual = 1 it must not be o_cache (INVALID_ARG); it may be
+ *                    x itself (the sum is then formed in place, as the last launch)
  * Errors: as dare_layer_step; INVALID_ARG when no block is attached.
  */
 dare_status dare_block_step(dare_ctx* ctx, int mode, float threshold, int batch,

@@ -25,6 +25,9 @@ EXPORTS = (
     "dare_k_norm", "dare_k_residual_add",
     "dare_set_threshold_rule", "dare_get_thresholds", "dare_drift_stats_enable", "dare_drift_stats_read",
     "dare_allocate_quantiles", "dare_policy_mode", "dare_k_quantile_mask", "dare_set_prefix",
+    "dare_model_create", "dare_model_set_layer", "dare_model_set_io", "dare_model_set_rule",
+    "dare_model_set_prefix", "dare_model_step", "dare_model_logits", "dare_model_layer",
+    "dare_model_destroy", "dare_model_last_error",
 )
 RULE_SCORE, RULE_QUANTILE = 0, 1
 NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2
@@ -53,6 +56,20 @@ class DareBlockConfig(ctypes.Structure):
         ("eps", ctypes.c_float),
         ("rope_base", ctypes.c_float),
         ("residual", ctypes.c_int32),
+    ]
+
+
+class DareModelConfig(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("n_layers", ctypes.c_int32), ("hidden", ctypes.c_int32), ("n_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("ffn", ctypes.c_int32), ("vocab", ctypes.c_int32),
+        ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("norm_eps", ctypes.c_float),
+        ("rope_base", ctypes.c_float),
+        ("device", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
     ]
 
 
@@ -125,6 +142,27 @@ def lib():
     L.dare_allocate_quantiles.restype = i32
     L.dare_policy_mode.argtypes = [i32] * 5
     L.dare_policy_mode.restype = i32
+    L.dare_model_create.argtypes = [ctypes.POINTER(DareModelConfig), vp, ctypes.POINTER(vp)]
+    L.dare_model_create.restype = i32
+    L.dare_model_set_layer.argtypes = [vp, i32] + [vp] * 10
+    L.dare_model_set_layer.restype = i32
+    L.dare_model_set_io.argtypes = [vp, vp, vp, vp, vp]
+    L.dare_model_set_io.restype = i32
+    L.dare_model_set_rule.argtypes = [vp, i32]
+    L.dare_model_set_rule.restype = i32
+    L.dare_model_set_prefix.argtypes = [vp, i32]
+    L.dare_model_set_prefix.restype = i32
+    L.dare_model_step.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float), i32, i32,
+                                  vp, vp, vp, vp, vp]
+    L.dare_model_step.restype = i32
+    L.dare_model_logits.argtypes = [vp, vp, vp, i32, vp, vp]
+    L.dare_model_logits.restype = i32
+    L.dare_model_layer.argtypes = [vp, i32]
+    L.dare_model_layer.restype = vp
+    L.dare_model_destroy.argtypes = [vp]
+    L.dare_model_destroy.restype = i32
+    L.dare_model_last_error.argtypes = [vp]
+    L.dare_model_last_error.restype = ctypes.c_char_p
     L.dare_set_prefix.argtypes = [vp, i32]
     L.dare_set_prefix.restype = i32
     L.dare_k_quantile_mask.argtypes = [vp, i32, i32, f32, i32, vp, vp, vp, vp, vp]
@@ -165,6 +203,15 @@ def dare_version():
 
 class DareLayer:
     """dare_create / dare_layer_step / dare_destroy for one layer's weights."""
+
+    @classmethod
+    def view(cls, ctx_ptr, device):
+        """A non-owning handle on a context that something else owns (a model's layer)."""
+        self = cls.__new__(cls)
+        self._ctx = ctypes.c_void_p(ctx_ptr)
+        self.device = device
+        self._borrowed = True
+        return self
 
     def __init__(self, wq, wk, wv, wo, n_heads, max_batch, max_seq, score_head=0, stream=None):
         import torch
@@ -244,9 +291,82 @@ class DareLayer:
         return mean.value, count.value
 
     def destroy(self):
-        if self._ctx:
+        if self._ctx and not getattr(self, "_borrowed", False):
             lib().dare_destroy(self._ctx)
-            self._ctx = ctypes.c_void_p()
+        self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class DareModel:
+    """dare_model_*: a masked-diffusion model of DARE layers.  Weights are torch tensors on
+    the GPU; they are copied at the set_* calls."""
+
+    def __init__(self, n_layers, hidden, n_heads, ffn, vocab, max_batch, max_seq, dtype, norm_eps=1e-5,
+                 rope_base=10000.0, device=None, stream=None):
+        import torch
+        self.device = device or torch.device("cuda", torch.cuda.current_device())
+        self.dtype = dtype
+        self.cfg = DareModelConfig(ctypes.sizeof(DareModelConfig), n_layers, hidden, n_heads, hidden // n_heads,
+                                   ffn, vocab, max_batch, max_seq, dtype, norm_eps, rope_base,
+                                   self.device.index or 0, 0)
+        self._m = ctypes.c_void_p()
+        st = lib().dare_model_create(ctypes.byref(self.cfg), _stream(stream), ctypes.byref(self._m))
+        self._check(st, created=False)
+
+    def _check(self, st, created=True):
+        if st != DARE_OK:
+            msg = lib().dare_model_last_error(self._m if created else None)
+            raise DareError(st, msg.decode() if msg else "")
+
+    def set_layer(self, layer, attn_gain, wq, wk, wv, wo, ffn_gain, w_gate, w_up, w_down, stream=None):
+        self._check(lib().dare_model_set_layer(self._m, layer, _ptr(attn_gain), _ptr(wq), _ptr(wk), _ptr(wv),
+                                               _ptr(wo), _ptr(ffn_gain), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                               _stream(stream)))
+
+    def set_io(self, embed, final_gain, head=None, stream=None):
+        self._check(lib().dare_model_set_io(self._m, _ptr(embed), _ptr(final_gain), _ptr(head), _stream(stream)))
+
+    def set_rule(self, rule):
+        self._check(lib().dare_model_set_rule(self._m, rule))
+
+    def set_prefix(self, prefix_len):
+        self._check(lib().dare_model_set_prefix(self._m, prefix_len))
+
+    def step(self, modes, thresholds, ids, hidden_out=None, refreshed=None, trace=None, stream=None):
+        L = self.cfg.n_layers
+        batch, seq = ids.shape
+        if isinstance(modes, int):
+            modes = [modes] * L
+        if isinstance(thresholds, (int, float)):
+            thresholds = [float(thresholds)] * L
+        assert len(modes) == L and len(thresholds) == L
+        ma = (ctypes.c_int32 * L)(*modes)
+        ta = (ctypes.c_float * L)(*thresholds)
+        self._check(lib().dare_model_step(self._m, ma, ta, batch, seq, _ptr(ids), _ptr(hidden_out),
+                                          _ptr(refreshed), _ptr(trace), _stream(stream)))
+
+    def logits(self, hidden, rows, stream=None):
+        import torch
+        out = torch.empty((rows.numel(), self.cfg.vocab), dtype=_torch_dtype(self.dtype), device=self.device)
+        self._check(lib().dare_model_logits(self._m, _ptr(hidden), _ptr(rows), rows.numel(), _ptr(out),
+                                            _stream(stream)))
+        return out
+
+    def layer(self, index):
+        ptr = lib().dare_model_layer(self._m, index)
+        if not ptr:
+            raise IndexError("no such layer, or its weights are not set")
+        return DareLayer.view(ptr, self.device)
+
+    def destroy(self):
+        if self._m:
+            lib().dare_model_destroy(self._m)
+            self._m = ctypes.c_void_p()
 
     def __del__(self):
         try:

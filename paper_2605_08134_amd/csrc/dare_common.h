@@ -96,5 +96,11 @@ hipError_t launch_norm(int dtype, int kind, const void* x, const void* gain, con
                        int n_rows, int d, void* out, int seq, int prefix, hipStream_t s);
 hipError_t launch_residual_add(int dtype, const void* x, const void* o, void* out, long n_elems,
                                hipStream_t s);
+hipError_t launch_residual_rows(int dtype, void* x, const void* f, int n_rows, int d, const int32_t* idx,
+                                hipStream_t s);
+hipError_t launch_gather_rows(const void* src, void* dst, const int32_t* ids, int n_rows, int n_src,
+                              int row_bytes, hipStream_t s);
+hipError_t launch_swiglu(int dtype, void* gate, const void* up, int n_rows, int width, const int32_t* idx,
+                         hipStream_t s);
 
 }  // namespace dare

@@ -477,7 +477,7 @@ hipError_t launch_gemm_bf16_cfg(const GemmArgs& g, int cfg, hipStream_t s) {
   if (g.n % 256 == 0 && tiles(256, 256) >= 512) return launch_fixed<256, 256, 2, 4, 2>(g, s);
   if (g.n % 192 == 0 && tiles(256, 192) >= 224) return launch_fixed<256, 192, 4, 2, 2>(g, s);
   if (g.n % 256 == 0 && tiles(256, 256) >= 224) return launch_fixed<256, 256, 2, 4, 2>(g, s);
-  if (g.n % 128 == 0 && tiles(128, 128) >= 64) return launch_fixed<128, 128, 4, 2, 4>(g, s);
+  if (g.m_max > 64 && g.n % 128 == 0 && tiles(128, 128) >= 64) return launch_fixed<128, 128, 4, 2, 4>(g, s);
   return launch_fixed<64, 64, 2, 2, 4>(g, s);
 }
 

@@ -140,7 +140,38 @@ __global__ void __launch_bounds__(256) residual_add_kernel(const T* __restrict__
   }
 }
 
+// x[t, :] += f[t, :] for the listed rows (a frozen prefix leaves the other rows alone).
+template <typename T>
+__global__ void __launch_bounds__(256) residual_rows_kernel(T* __restrict__ x, const T* __restrict__ f, int n_rows,
+                                                            int d, const int32_t* __restrict__ idx) {
+  const int groups = d >> 3;
+  for (int r = blockIdx.x; r < n_rows; r += gridDim.x) {
+    const long tok = (long)idx[r];
+    for (int g = threadIdx.x; g < groups; g += 256) {
+      float a[8], b[8];
+      load8(x + tok * d + g * 8, a);
+      load8(f + tok * d + g * 8, b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] += b[e];
+      store8(x + tok * d + g * 8, a);
+    }
+  }
+}
+
 }  // namespace
+
+hipError_t launch_residual_rows(int dtype, void* x, const void* f, int n_rows, int d, const int32_t* idx,
+                                hipStream_t s) {
+  if (n_rows == 0) return hipSuccess;
+  const int grid = n_rows < 8192 ? n_rows : 8192;
+  if (dtype == DARE_BF16)
+    hipLaunchKernelGGL(residual_rows_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, static_cast<bf16_t*>(x),
+                       static_cast<const bf16_t*>(f), n_rows, d, idx);
+  else
+    hipLaunchKernelGGL(residual_rows_kernel<float>, dim3(grid), dim3(256), 0, s, static_cast<float*>(x),
+                       static_cast<const float*>(f), n_rows, d, idx);
+  return hipGetLastError();
+}
 
 hipError_t launch_norm(int dtype, int kind, const void* x, const void* gain, const void* bias, float eps,
                        int n_rows, int d, void* out, int seq, int prefix, hipStream_t s) {

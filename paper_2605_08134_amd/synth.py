@@ -89,6 +89,32 @@ def make_norm_params(seed, hidden, dtype):
     return {"gain": _store(gain, dtype), "bias": _store(bias, dtype)}
 
 
+def make_model_params(seed, n_layers, hidden, ffn, vocab, dtype, with_head=True):
+    """Random-init weights of a masked-diffusion model: projection matrices ~ N(0, 0.02^2),
+    normalisation gains ~ 1 + 0.1 N(0,1), token embedding ~ N(0,1).  float32 arrays holding
+    values representable in `dtype`."""
+    rng = np.random.Generator(np.random.PCG64(seed + 15485863))
+    nrm = lambda *shape, std=WEIGHT_STD: _store(rng.standard_normal(shape, dtype=np.float32) * np.float32(std), dtype)
+    gain = lambda: _store(np.float32(1.0) + np.float32(0.1) * rng.standard_normal(hidden, dtype=np.float32), dtype)
+    layers = []
+    for _ in range(n_layers):
+        layers.append(dict(attn_gain=gain(), wq=nrm(hidden, hidden), wk=nrm(hidden, hidden), wv=nrm(hidden, hidden),
+                           wo=nrm(hidden, hidden), ffn_gain=gain(), w_gate=nrm(hidden, ffn), w_up=nrm(hidden, ffn),
+                           w_down=nrm(ffn, hidden)))
+    params = dict(embed=nrm(vocab, hidden, std=1.0), final_gain=gain(), layers=layers)
+    if with_head:
+        params["head"] = nrm(hidden, vocab)
+    return params
+
+
+def make_ids(seed, batch, seq, vocab, prompt_len, mask_id):
+    """A prompt of uniform random ids followed by mask ids, int32 [batch, seq]."""
+    rng = np.random.Generator(np.random.PCG64(seed + 32452843))
+    ids = np.full((batch, seq), mask_id, dtype=np.int32)
+    ids[:, :prompt_len] = rng.integers(0, vocab - 1, (batch, prompt_len))
+    return ids
+
+
 # Layer shapes of the workloads.  "tiny" is the small fp32 case; "llada8b" is one
 # LLaDA-8B-shaped layer at 512 prompt + 512 generated tokens; "llada8b_b8" is the
 # same layer at 2048 tokens and 8 sequences with per-sequence perturbed fractions.

@@ -21,7 +21,7 @@ def L():
 
 def _declared():
     names = set()
-    for h in ("dare.h", "dare_kernels.h"):
+    for h in ("dare.h", "dare_kernels.h", "dare_model.h"):
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names |= set(re.findall(r"\b(dare_[a-z0-9_]+)\s*\(", text))

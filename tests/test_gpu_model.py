@@ -1,0 +1,202 @@
+"""GPU parity of the model runtime (dare_model_*) against the model oracle.
+
+The model keeps its caches inside, so the oracle keeps its own and both advance step by
+step.  Each layer is checked on the residual stream the GPU itself fed it (the `trace`
+output): the oracle runs the layer's attention block and feed-forward on that input and
+its own caches, and the results are compared under the rules of parity_util.  Thresholds
+sit in the wide gap between the drift of unchanged tokens (0 up to rounding) and of
+changed ones, so the decisions are the same on both sides; refreshed counts are compared
+exactly."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dare_oracle as orc
+from oracle import dllm_oracle as dl
+from paper_2605_08134_amd import synth
+import parity_util as pu
+from parity_util import dev, host
+
+pytestmark = pytest.mark.gpu
+
+EPS, ROPE = 1e-5, 10000.0
+
+
+def _build(Bm, params, cfg, dtype):
+    dt = Bm.DARE_BF16 if dtype == "bf16" else Bm.DARE_F32
+    m = Bm.DareModel(cfg["L"], cfg["d"], cfg["H"], cfg["ffn"], cfg["V"], cfg["B"], cfg["T"], dt, EPS, ROPE)
+    for l, lp in enumerate(params["layers"]):
+        m.set_layer(l, *[dev(lp[k], dtype) for k in ("attn_gain", "wq", "wk", "wv", "wo", "ffn_gain", "w_gate",
+                                                      "w_up", "w_down")])
+    m.set_io(dev(params["embed"], dtype), dev(params["final_gain"], dtype),
+             dev(params["head"], dtype) if "head" in params else None)
+    return m
+
+
+def _zero_caches(cfg):
+    z = np.zeros((cfg["B"], cfg["T"], cfg["d"]))
+    return [dict(q_prev=np.zeros((cfg["B"], cfg["T"], cfg["d"] // cfg["H"])), k_cache=z, v_cache=z, o_cache=z)
+            for _ in range(cfg["L"])]
+
+
+def _gpu_step(m, cfg, dtype, modes, taus, ids):
+    td = pu.tdtype(dtype)
+    n = cfg["B"] * cfg["T"] * cfg["d"]
+    hidden = torch.full((cfg["B"], cfg["T"], cfg["d"]), float("nan"), dtype=td, device="cuda")
+    refreshed = torch.full((cfg["L"], cfg["B"]), -1, dtype=torch.int32, device="cuda")
+    trace = torch.full((2 * cfg["L"] + 1, n), float("nan"), dtype=td, device="cuda")
+    m.step(modes, taus, dev(ids), hidden, refreshed, trace)
+    torch.cuda.synchronize()
+    tr = host(trace).reshape(2 * cfg["L"] + 1, cfg["B"], cfg["T"], cfg["d"])
+    return host(hidden), host(refreshed), tr
+
+
+def _check_step(cfg, dtype, params, caches, modes, taus, ids, hidden, refreshed, tr, prefix=0, quantile=False):
+    """Layer by layer on the GPU's own residual stream; returns the oracle's new caches."""
+    storage = "bf16" if dtype == "bf16" else None
+    tol = pu.TOL[dtype]
+    active = np.ones((cfg["B"], cfg["T"]), dtype=bool)
+    active[:, :prefix] = False
+    new_caches = []
+    for l, lp in enumerate(params["layers"]):
+        c = caches[l]
+        x_in, x_mid, x_out = tr[2 * l], tr[2 * l + 1], tr[2 * l + 2]
+        r = orc.block_step(modes[l], taus[l], x_in, "rms", lp["attn_gain"], None, EPS, lp["wq"], lp["wk"], lp["wv"],
+                           lp["wo"], c["q_prev"], c["k_cache"], c["v_cache"], c["o_cache"], cfg["H"], storage=storage,
+                           rope_base=ROPE, residual=True, quantile=quantile, prefix=prefix)
+        assert np.array_equal(refreshed[l], r["sel_count"]), "layer %d refreshed %s, oracle %s" % (
+            l, refreshed[l], r["sel_count"])
+        rms_o = float(np.sqrt(np.mean(r["exact"]["out"] ** 2)))
+        want_mid = r["exact"]["block_out"]
+        if dtype == "f32":
+            assert np.max(np.abs(x_mid - want_mid)) <= 1e-4 * rms_o, "layer %d attention block" % l
+        else:
+            ex = np.abs(x_mid - want_mid) - pu.half_ulp_bf16(want_mid) - pu.half_ulp_bf16(r["exact"]["out"])
+            assert np.max(ex) <= tol * rms_o, "layer %d attention block: %g" % (l, np.max(ex) / rms_o)
+        got_ffn, exact_ffn = dl.ffn_block(x_mid, lp["ffn_gain"], EPS, lp["w_gate"], lp["w_up"], lp["w_down"], storage,
+                                          rows=active if prefix else None)
+        f = exact_ffn - x_mid
+        rms_f = float(np.sqrt(np.mean(f[active] ** 2)))
+        if dtype == "f32":
+            assert np.max(np.abs(x_out - exact_ffn)) <= 1e-4 * rms_f, "layer %d feed-forward" % l
+        else:
+            ex = np.abs(x_out - exact_ffn) - pu.half_ulp_bf16(exact_ffn) - pu.half_ulp_bf16(f)
+            assert np.max(ex) <= tol * rms_f, "layer %d feed-forward: %g" % (l, np.max(ex) / rms_f)
+        if prefix:
+            assert np.array_equal(x_out[:, :prefix], x_mid[:, :prefix])
+        new_caches.append({k: r[k] for k in ("q_prev", "k_cache", "v_cache", "o_cache")})
+    y = orc.rms_norm(tr[-1], params["final_gain"], EPS)
+    if dtype == "f32":
+        assert pu.rel_err(hidden, y) <= 1e-5
+    else:
+        assert np.all(np.abs(hidden - y) <= pu.half_ulp_bf16(y) + 1e-5 * np.maximum(np.abs(y), 1.0))
+    return new_caches
+
+
+@pytest.fixture(scope="module")
+def Bm():
+    from paper_2605_08134_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_model_blockwise_steps(Bm, dtype):
+    cfg = dict(L=3, d=256, H=4, ffn=512, V=320, B=2, T=48)
+    params = synth.make_model_params(5, cfg["L"], cfg["d"], cfg["ffn"], cfg["V"], dtype)
+    m = _build(Bm, params, cfg, dtype)
+    mask_id = cfg["V"] - 1
+    ids = synth.make_ids(5, cfg["B"], cfg["T"], cfg["V"], 16, mask_id)
+    rng = np.random.Generator(np.random.PCG64(17))
+    steps = dl.blockwise_schedule(16, 32, 16, 1, rng)
+    caches = _zero_caches(cfg)
+    L = cfg["L"]
+    plan = [([orc.MODE_DENSE] * L, [0.0] * L)]
+    for mode in (orc.MODE_KVO, orc.MODE_KV, orc.MODE_O, [orc.MODE_DENSE, orc.MODE_KVO, orc.MODE_O]):
+        plan.append(([mode] * L if isinstance(mode, int) else mode, [1e-3] * L))
+    for t, (modes, taus) in enumerate(plan):
+        if t > 0:
+            for b in range(cfg["B"]):
+                ids[b, steps[t - 1]] = rng.integers(0, mask_id)
+        hidden, refreshed, tr = _gpu_step(m, cfg, dtype, modes, taus, ids)
+        assert np.array_equal(tr[0], dl.embed(ids, params["embed"]).astype(np.float32))
+        caches = _check_step(cfg, dtype, params, caches, modes, taus, ids, hidden, refreshed, tr)
+        if t > 0 and modes[0] != orc.MODE_DENSE:
+            assert (refreshed[0] == 1).all()          # layer 0: only the token whose id changed
+    # the same ids again: nothing drifts, everything is reused, the output does not move
+    h2, r2, _ = _gpu_step(m, cfg, dtype, [orc.MODE_KVO] * L, [0.0] * L, ids)
+    assert (r2 == 0).all() and np.array_equal(h2, hidden)
+    # logits of a few rows
+    rows = np.array([0, 17, 95], dtype=np.int32)
+    lg = host(m.logits(dev(hidden, dtype), dev(rows)))
+    want = dl.logits(hidden.reshape(-1, cfg["d"])[rows], params["head"])
+    pu.assert_close(lg, want, dtype)
+    m.destroy()
+
+
+def test_small_model_prefix_and_quantile_rule(Bm):
+    dtype = "f32"
+    cfg = dict(L=2, d=128, H=2, ffn=256, V=192, B=2, T=40)
+    params = synth.make_model_params(6, cfg["L"], cfg["d"], cfg["ffn"], cfg["V"], dtype, with_head=False)
+    m = _build(Bm, params, cfg, dtype)
+    ids = synth.make_ids(6, cfg["B"], cfg["T"], cfg["V"], 12, cfg["V"] - 1)
+    L = cfg["L"]
+    caches = _zero_caches(cfg)
+    hidden, refreshed, tr = _gpu_step(m, cfg, dtype, [orc.MODE_DENSE] * L, [0.0] * L, ids)
+    caches = _check_step(cfg, dtype, params, caches, [orc.MODE_DENSE] * L, [0.0] * L, ids, hidden, refreshed, tr)
+    m.set_prefix(12)                                   # the prompt is frozen from here on
+    ids[:, 20] = 3
+    ids[:, 31] = 5
+    modes, taus = [orc.MODE_KVO, orc.MODE_KV], [1e-3, 1e-3]
+    hidden, refreshed, tr = _gpu_step(m, cfg, dtype, modes, taus, ids)
+    caches = _check_step(cfg, dtype, params, caches, modes, taus, ids, hidden, refreshed, tr, prefix=12)
+    assert (refreshed[0] == 2).all()
+    # quantile rule: half of the 28 tokens that are not frozen are reused in every layer
+    m.set_rule(Bm.RULE_QUANTILE)
+    ids[:, 25] = 7
+    hidden, refreshed, tr = _gpu_step(m, cfg, dtype, [orc.MODE_KVO] * L, [0.5] * L, ids)
+    assert (refreshed <= 14).all() and (refreshed[0] >= 1).all()
+    with pytest.raises(Bm.DareError):
+        m.step([orc.MODE_KVO] * L, [1.5] * L, dev(ids))
+    m.destroy()
+
+
+def test_model_argument_errors(Bm):
+    with pytest.raises(Bm.DareError):
+        Bm.DareModel(1, 100, 2, 128, 64, 1, 8, Bm.DARE_F32)          # hidden not a multiple of 64
+    m = Bm.DareModel(2, 128, 2, 128, 64, 1, 8, Bm.DARE_F32)
+    ids = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(Bm.DareError):
+        m.step(0, 0.0, ids)                                           # no weights yet
+    with pytest.raises(IndexError):
+        m.layer(0)
+    m.destroy()
+
+
+def test_out_of_range_ids_embed_as_zero(Bm):
+    cfg = dict(L=1, d=128, H=2, ffn=128, V=64, B=1, T=8)
+    params = synth.make_model_params(7, 1, 128, 128, 64, "f32", with_head=False)
+    m = _build(Bm, params, cfg, "f32")
+    ids = np.array([[0, 63, 64, -1, 5, 1000, 2, 3]], dtype=np.int32)
+    _, _, tr = _gpu_step(m, cfg, "f32", [0], [0.0], ids)
+    want = np.where(((ids >= 0) & (ids < 64))[:, :, None], params["embed"][np.clip(ids, 0, 63)], 0.0)
+    assert np.array_equal(tr[0], want.astype(np.float32))
+    m.destroy()
+
+
+def test_two_layers_at_llada_width(Bm):
+    """Full layer width (hidden 4096, 32 x 128, feed-forward 12288), bf16, 2 layers, 256 tokens."""
+    dtype = "bf16"
+    cfg = dict(L=2, d=4096, H=32, ffn=12288, V=512, B=1, T=256)
+    params = synth.make_model_params(8, cfg["L"], cfg["d"], cfg["ffn"], cfg["V"], dtype, with_head=False)
+    m = _build(Bm, params, cfg, dtype)
+    ids = synth.make_ids(8, 1, 256, 512, 128, 511)
+    caches = _zero_caches(cfg)
+    hidden, refreshed, tr = _gpu_step(m, cfg, dtype, [0, 0], [0.0, 0.0], ids)
+    caches = _check_step(cfg, dtype, params, caches, [0, 0], [0.0, 0.0], ids, hidden, refreshed, tr)
+    ids[0, [130, 141, 150, 200]] = [1, 2, 3, 4]
+    modes, taus = [orc.MODE_KVO, orc.MODE_KVO], [1e-3, 1e-3]
+    hidden, refreshed, tr = _gpu_step(m, cfg, dtype, modes, taus, ids)
+    _check_step(cfg, dtype, params, caches, modes, taus, ids, hidden, refreshed, tr)
+    assert refreshed[0].tolist() == [4]
+    m.destroy()
