@@ -34,6 +34,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--quick", action="store_true", help="headline point and dense only")
+    ap.add_argument("--model-steps", type=int, default=48,
+                    help="denoising steps of the 32-layer model leg (0 skips it)")
+    ap.add_argument("--only-model", action="store_true",
+                    help="run only the 32-layer model leg (for profiler passes)")
     ap.add_argument("--only-dominant", action="store_true",
                     help="run only the dominant-kernel loop (for profiler passes)")
     return ap.parse_args()
@@ -55,6 +59,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.only_model:
+        print(json.dumps({"model": model_leg(torch, B, np, dev, max(1, args.model_steps))}))
+        return
 
     cfg = dict(synth.CONFIGS["llada8b"])
     Bn, T, d, H, Dh = cfg["batch"], cfg["seq"], cfg["hidden"], cfg["n_heads"], cfg["head_dim"]
@@ -225,6 +233,13 @@ def main():
         peaks = measured_peaks(torch, B, dev, d)
         roofline_other += other_kernels_at_c2(torch, B, np, dev, d, H, Dh)
 
+    # ---- the rows beyond the layer step: block, quantile rule, frozen prefix, whole model ----
+    features = model = None
+    if not args.quick:
+        features = feature_legs(torch, B, synth, wdev, weights, seed, xa, xb, Bn, T, d, H, Dh, tau, ms_dense)
+        if args.model_steps > 0:
+            model = model_leg(torch, B, np, dev, args.model_steps)
+
     # ---- CPU oracle on the host cores (reported baseline, not a target) ----------------------
     cpu = None
     if not args.no_cpu:
@@ -254,6 +269,8 @@ def main():
         "measured_peaks": peaks,
         "latency": latency,
         "cold_weights": cold,
+        "features": features,
+        "model": model,
         "cpu_baseline": cpu,
         "sweep": sweep,
     }
@@ -269,6 +286,107 @@ def _time_us(torch, fn, iters, warm=3):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / iters * 1e3
+
+
+def feature_legs(torch, B, synth, wdev, weights, seed, xa, xb, Bn, T, d, H, Dh, tau, ms_dense):
+    """The same layer with what the next rows add, each timed like the headline (KV+O at 80 %
+    reuse unless stated): the block (RMS norm, rotary embedding, residual sum), the quantile
+    rule (reuse rate 0.8), and a frozen prefix of half the sequence."""
+    dev = xa.device
+    layer = B.DareLayer(*wdev, n_heads=H, max_batch=Bn, max_seq=T)
+    gain = torch.from_numpy(synth.make_norm_params(seed, d, "bf16")["gain"]).to(torch.bfloat16).to(dev)
+    mask = torch.zeros((Bn, T), dtype=torch.uint8, device=dev)
+    out = torch.empty((Bn, T, d), dtype=torch.bfloat16, device=dev)
+    cnt = torch.zeros((Bn,), dtype=torch.int32, device=dev)
+
+    def timed(call, steps=100):
+        st = layer.new_state(Bn, T)
+        call(B.MODE_DENSE, 0.0, xa, st)
+        def run(n):
+            for i in range(n):
+                call(run.mode, run.tau, xb if i % 2 == 0 else xa, st)
+        def go(mode, t):
+            run.mode, run.tau = mode, t
+            us = _time_us(torch, run, steps, warm=10)
+            return us, float(mask.float().mean().item())
+        return go
+
+    res = {}
+    plain = timed(lambda mode, t, x, st: layer.layer_step(mode, t, x, st["q_prev"], st["k_cache"], st["v_cache"],
+                                                          st["o_cache"], st["o_cache"], mask, None, cnt, None))
+    layer.block_attach("rms", gain, None, 1e-5, 10000.0, True)
+    block = timed(lambda mode, t, x, st: layer.block_step(mode, t, x, st["q_prev"], st["k_cache"], st["v_cache"],
+                                                          st["o_cache"], out, mask, None, cnt, None))
+    us_d, _ = block(B.MODE_DENSE, 0.0)
+    us_k, r = block(B.MODE_KVO, tau)
+    res["block_rms_rope_residual"] = {"kvo_us": us_k, "dense_us": us_d, "reuse": r, "vs_dense": us_k / us_d}
+    layer.set_threshold_rule(B.RULE_QUANTILE)
+    us_q, r = plain(B.MODE_KVO, 0.8)
+    res["quantile_rule_phi_0.8"] = {"kvo_us": us_q, "reuse": r, "vs_dense": us_q / (ms_dense * 1e3)}
+    layer.set_threshold_rule(B.RULE_SCORE)
+    layer.set_prefix(T // 2)
+    us_pd, _ = plain(B.MODE_DENSE, 0.0)
+    us_pk, r = plain(B.MODE_KVO, tau)
+    res["frozen_prefix_%d" % (T // 2)] = {"kvo_us": us_pk, "dense_us": us_pd, "reuse_incl_frozen": r,
+                                          "vs_dense_with_prefix": us_pk / us_pd,
+                                          "dense_with_prefix_vs_dense": us_pd / (ms_dense * 1e3)}
+    layer.destroy()
+    return res
+
+
+def model_leg(torch, B, np, dev, n_steps):
+    """A random-init LLaDA-8B-shaped masked-diffusion model: 32 layers, hidden 4096, 32 x 128
+    heads, SwiGLU feed-forward 12288, RMS norm, rotary embedding, vocabulary 126464, bf16.
+    512 prompt ids followed by 512 mask ids; block-wise schedule with blocks of 32; every
+    denoising step replaces one seeded random mask position of the current block by a random
+    id.  Weights come from torch's seeded generator (timing and reuse statistics only; the
+    parity tests use the numpy generator).  DARE (KV+O, threshold 1e-3) runs in every layer;
+    the same schedule is run again with every layer dense.  Reuse here is not injected: it is
+    what one changed token does to the other tokens' queries in a random network."""
+    L, d, H, ffn, V, T, P = 32, 4096, 32, 12288, 126464, 1024, 512
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20260508)
+    rn = lambda *shape, std=0.02: (torch.randn(shape, device=dev, generator=gen) * std).to(torch.bfloat16)
+    gain = lambda: (1.0 + 0.1 * torch.randn((d,), device=dev, generator=gen)).to(torch.bfloat16)
+    m = B.DareModel(L, d, H, ffn, V, 1, T, B.DARE_BF16, 1e-5, 10000.0)
+    for l in range(L):
+        m.set_layer(l, gain(), rn(d, d), rn(d, d), rn(d, d), rn(d, d), gain(), rn(d, ffn), rn(d, ffn), rn(ffn, d))
+    m.set_io(rn(V, d, std=1.0), gain(), None)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.PCG64(20260508))
+    mask_id = V - 1
+    ids0 = np.full((1, T), mask_id, dtype=np.int32)
+    ids0[0, :P] = rng.integers(0, mask_id, P)
+    order = []
+    for b0 in range(P, T, 32):
+        order += list(b0 + rng.permutation(32))
+    new_ids = rng.integers(0, mask_id, len(order))
+    refreshed = torch.zeros((L, 1), dtype=torch.int32, device=dev)
+    out = {}
+    for name, mode, thr in (("kvo", B.MODE_KVO, 1e-3), ("dense", B.MODE_DENSE, 0.0)):
+        ids = torch.from_numpy(ids0.copy()).to(dev)
+        m.step(B.MODE_DENSE, 0.0, ids)               # fills every layer's caches
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_steps + 1)]
+        counts = []
+        ev[0].record()
+        for t in range(n_steps):
+            ids[0, order[t]] = int(new_ids[t])
+            m.step(mode, thr, ids, None, refreshed)
+            ev[t + 1].record()
+            counts.append(refreshed.clone())
+        torch.cuda.synchronize()
+        us = np.array([ev[t].elapsed_time(ev[t + 1]) * 1e3 for t in range(n_steps)])
+        ref = torch.stack(counts).float().cpu().numpy()[:, :, 0]          # [steps, layers]
+        out[name] = {"step_us_median": float(np.median(us)), "layer_us_mean": float(np.mean(us) / L),
+                     "reuse_mean": float(1.0 - ref.mean() / T),
+                     "reuse_by_layer_first_mid_last": [float(1.0 - ref[:, l].mean() / T) for l in (0, L // 2, L - 1)]}
+    out["layer_latency_vs_dense"] = out["kvo"]["layer_us_mean"] / out["dense"]["layer_us_mean"]
+    out["config"] = {"layers": L, "hidden": d, "heads": H, "ffn": ffn, "vocab": V, "seq": T, "prompt": P,
+                     "block": 32, "steps_timed": n_steps, "threshold": 1e-3,
+                     "note": "per-layer latency includes the layer's feed-forward, which DARE does not touch"}
+    m.destroy()
+    return out
 
 
 def cold_weights(torch, B, layer0, wdev, xa, xb, Bn, T, d, H, tau, n_layers=8):

@@ -90,6 +90,27 @@ constexpr int smem_bytes() {
   return STAGES * (BM + BN) * ROW_BYTES;
 }
 
+// Four neighbouring output columns col .. col + 3 (col a multiple of 4) of token tok: the
+// fp32 copy of the scored columns (before any rotation), then rotation, rounding and the
+// store into the column's segment.
+__device__ __forceinline__ void store4(const GemmDev& p, float* c32, long tok, int col, float v0, float v1,
+                                       float v2, float v3) {
+  if (c32 && col < p.c32_cols) {
+    const f32x4 o = {v0, v1, v2, v3};
+    *reinterpret_cast<f32x4*>(c32 + tok * p.c32_cols + col) = o;
+  }
+  const int seg = col / p.seg_n;
+  bf16_t* cbase = seg == 0 ? p.c0 : (seg == 1 ? p.c1 : p.c2);
+  if (!cbase) return;
+  if (p.rope && col < p.rope_cols) rope_rotate4(p.rope, p.rope_dh, p.rope_seq, tok, col, v0, v1, v2, v3);
+  bf16x4 o;
+  o[0] = (bf16_t)v0;
+  o[1] = (bf16_t)v1;
+  o[2] = (bf16_t)v2;
+  o[3] = (bf16_t)v3;
+  *reinterpret_cast<bf16x4*>(cbase + tok * p.ldc + (col - seg * p.seg_n)) = o;
+}
+
 // One output tile of C for m rows, computed by a team of WAVES_M * WAVES_N waves; tid
 // is the thread's index within the team and smem the team's own
 // smem_bytes<BM, BN, STAGES>() bytes.  A workgroup is one team (nsub = 1) or nsub teams
@@ -295,27 +316,83 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
       for (int g = 0; g < 4; ++g) {
         const int col = n0 + wave_n * WN + j * 32 + g * 8 + half * 4;
         if (col >= p.n) continue;
-        float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1];
-        float v2 = acc[i][j][g * 4 + 2], v3 = acc[i][j][g * 4 + 3];
-        if (c32 && col < p.c32_cols) {  // the scored columns: before any rotation
-          f32x4 o = {v0, v1, v2, v3};
-          *reinterpret_cast<f32x4*>(c32 + tok * p.c32_cols + col) = o;
-        }
-        const int seg = col / p.seg_n;
-        bf16_t* cbase = seg == 0 ? p.c0 : (seg == 1 ? p.c1 : p.c2);
-        if (cbase) {
-          if (p.rope && col < p.rope_cols) rope_rotate4(p.rope, p.rope_dh, p.rope_seq, tok, col, v0, v1, v2, v3);
-          bf16x4 o;
-          o[0] = (bf16_t)v0;
-          o[1] = (bf16_t)v1;
-          o[2] = (bf16_t)v2;
-          o[3] = (bf16_t)v3;
-          *reinterpret_cast<bf16x4*>(cbase + tok * p.ldc + (col - seg * p.seg_n)) = o;
-        }
+        store4(p, c32, tok, col, acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2],
+               acc[i][j][g * 4 + 3]);
       }
     }
   }
 }
+
+// ---- very few rows (at most 16 TMS): a stream over the weight matrix ------------------
+// With a handful of refreshed rows (one or two tokens unmasked per denoising step) the
+// projection is a matrix-vector product in disguise: what matters is that every CU pulls on
+// the weight stream at once and that each weight byte is read once.  A workgroup owns 16
+// output columns for the whole of k; its NW waves take contiguous ranges of k, load their
+// weight and row fragments straight into registers (no LDS: a fragment is used by one wave
+// only), 16 k-steps of 32 in flight per wave (8 with two row blocks), multiply with v_mfma_f32_16x16x32_bf16
+// (weight fragment first, so a lane again owns one row and four neighbouring columns), and
+// the partial sums of the waves are added in wave order through LDS.
+template <int NW, int TMS>
+__device__ __forceinline__ void skinny_tile(const GemmDev& p, const int m, unsigned char* smem, const int tid) {
+  constexpr int UNR = TMS == 1 ? 16 : 8;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int groups = p.n >> 4;
+  const int steps = p.k >> 5;
+  const int spw = (steps + NW - 1) / NW;
+  const int s0 = wave * spw;
+  const int s1 = s0 + spw < steps ? s0 + spw : steps;
+  const bf16_t* xrow[TMS];
+  long tok[TMS];
+#pragma unroll
+  for (int t = 0; t < TMS; ++t) {
+    int r = t * 16 + l16;
+    r = r < m ? r : m - 1;
+    tok[t] = p.idx ? (long)p.idx[r] : (long)r;
+    xrow[t] = p.a + tok[t] * p.lda + kq * 8;
+  }
+  f32x4* red = reinterpret_cast<f32x4*>(smem);  // [NW][TMS][64]
+  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const int n0 = grp << 4;
+    const bf16_t* wrow = p.wt + (long)(n0 + l16) * p.k + kq * 8;
+    f32x4 acc[TMS];
+#pragma unroll
+    for (int t = 0; t < TMS; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = s0; s < s1; s += UNR) {
+      bf16x8 wf[UNR], xf[TMS][UNR];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const bool live = s + u < s1;
+        const int ks = (live ? s + u : s0) << 5;
+        wf[u] = *reinterpret_cast<const bf16x8*>(wrow + ks);
+#pragma unroll
+        for (int t = 0; t < TMS; ++t) xf[t][u] = *reinterpret_cast<const bf16x8*>(xrow[t] + ks);
+        if (!live) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) wf[u][e] = (bf16_t)0.0f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u)
+#pragma unroll
+        for (int t = 0; t < TMS; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], xf[t][u], acc[t], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < TMS; ++t) red[(wave * TMS + t) * 64 + lane] = acc[t];
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int t = 0; t < TMS; ++t) {
+        f32x4 v = red[t * 64 + lane];
+        for (int w = 1; w < NW; ++w) v += red[(w * TMS + t) * 64 + lane];
+        if (t * 16 + l16 < m) store4(p, p.c32, tok[t], n0 + kq * 4, v[0], v[1], v[2], v[3]);
+      }
+    }
+    __syncthreads();
+  }
+}
+constexpr int kSkinnyRows = 32;
 
 // ---- one tile shape, chosen on the host (row count known or bounded) --------------
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
@@ -333,6 +410,14 @@ __global__ void __launch_bounds__(256) gemm_bf16_rows_kernel(GemmDev p) {
   static_assert(smem_bytes<128, 128, 2>() <= kRowsSmem, "shared buffer too small");
   const int m = p.m_dev ? *p.m_dev : p.m_max;
   if (m <= 0) return;
+  // Up to 32 rows: the register-fed stream (measured at n = 4096: 11-15 us against 17-22 us
+  // for the 64 x 64 tiles, which give that output width only 64 workgroups).  The wide
+  // kernel below keeps its 64 x 64 tiles for few rows: with 192 column tiles they already
+  // stream the weights at 5 TB/s.
+  if (m <= kSkinnyRows) {
+    if (m <= 16) skinny_tile<4, 1>(p, m, smem, threadIdx.x); else skinny_tile<4, 2>(p, m, smem, threadIdx.x);
+    return;
+  }
   // Up to 256 rows the projection is a stream over the weight matrix and what
   // matters is the number of workgroups pulling on it: 64 x 64 tiles (measured best
   // for 52..256 rows at n = 4096 and n = 12288).  Beyond that, 128 x 128 tiles with a

@@ -82,7 +82,7 @@ def test_rope_table(B, head_dim, base, n_pos):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("count", [None, 0, 77])
+@pytest.mark.parametrize("count", [None, 0, 9, 30, 77])
 def test_gemm_rope_epilogue(B, dtype, count):
     """Q | K | V projection with Q and K rotated, V not; the fp32 copy of the scored
     columns keeps the unrotated values.  Two sequences: position = token id mod seq."""

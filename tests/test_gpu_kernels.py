@@ -57,7 +57,7 @@ def test_gemm_all_rows(B, dtype, m, n, k, seg):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("count", [0, 1, 129, 205])
+@pytest.mark.parametrize("count", [0, 1, 16, 17, 32, 33, 129, 205])
 def test_gemm_selected_rows_device_count(B, dtype, count):
     r = _rng(count + 5)
     n_tok, k, n = 400, 128, 256
@@ -81,7 +81,7 @@ def test_gemm_selected_rows_device_count(B, dtype, count):
         assert_close(got[rows], want[rows], dtype)
 
 
-@pytest.mark.parametrize("n_tok,count", [(1024, 0), (1024, 1), (1024, 52), (1024, 100), (1024, 205),
+@pytest.mark.parametrize("n_tok,count", [(1024, 0), (1024, 1), (1024, 7), (1024, 16), (1024, 17), (1024, 32), (1024, 33), (1024, 52), (1024, 100), (1024, 205),
                                          (1024, 700), (1024, 1024), (3072, 2900)])
 def test_gemm_selected_rows_wide_output(B, n_tok, count):
     """Wide outputs (n >= 8192) take the 8-wave kernel, whose tile shape follows the
