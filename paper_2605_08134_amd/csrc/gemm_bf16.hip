@@ -392,7 +392,7 @@ __device__ __forceinline__ void skinny_tile(const GemmDev& p, const int m, unsig
     __syncthreads();
   }
 }
-constexpr int kSkinnyRows = 32;
+constexpr int kSkinnyRows = 32, kSkinnyMaxN = 8192;
 
 // ---- one tile shape, chosen on the host (row count known or bounded) --------------
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
@@ -404,31 +404,7 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDe
 }
 
 // ---- row count read on the device: the tile shape follows it -------------------------
-constexpr int kRowsSmem = smem_bytes<64, 64, 4>();  // 64 KiB: two workgroups per CU
-__global__ void __launch_bounds__(256) gemm_bf16_rows_kernel(GemmDev p) {
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[kRowsSmem];
-  static_assert(smem_bytes<128, 128, 2>() <= kRowsSmem, "shared buffer too small");
-  const int m = p.m_dev ? *p.m_dev : p.m_max;
-  if (m <= 0) return;
-  // Up to 32 rows: the register-fed stream (measured at n = 4096: 11-15 us against 17-22 us
-  // for the 64 x 64 tiles, which give that output width only 64 workgroups).  The wide
-  // kernel below keeps its 64 x 64 tiles for few rows: with 192 column tiles they already
-  // stream the weights at 5 TB/s.
-  if (m <= kSkinnyRows) {
-    if (m <= 16) skinny_tile<4, 1>(p, m, smem, threadIdx.x); else skinny_tile<4, 2>(p, m, smem, threadIdx.x);
-    return;
-  }
-  // Up to 256 rows the projection is a stream over the weight matrix and what
-  // matters is the number of workgroups pulling on it: 64 x 64 tiles (measured best
-  // for 52..256 rows at n = 4096 and n = 12288).  Beyond that, 128 x 128 tiles with a
-  // two-stage ring, which fit the same 64 KiB.
-  if (m <= 256)
-    gemm_tile<64, 64, 2, 2, 4>(p, m, smem, threadIdx.x);
-  else
-    gemm_tile<128, 128, 2, 2, 2>(p, m, smem, threadIdx.x);
-}
-
-// The same for wide outputs (the three projections in one launch), 8 waves and 128 KiB
+// One kernel for every projection of refreshed rows, 8 waves and 128 KiB
 // of LDS.  What bounds a projection of few rows is the rate at which one CU pulls
 // operand tiles out of L2 (measured 45-80 GB/s per CU whatever the ring depth), so the
 // shape that wins moves the fewest bytes per CU while still using every CU:
@@ -448,6 +424,14 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
                 "shared buffer too small");
   const int m = p.m_dev ? *p.m_dev : p.m_max;
   if (m <= 0) return;
+  // Up to 32 rows and a narrow output (the output projection): the register-fed stream
+  // (measured at n = 4096: 11-15 us against 17 us for 64 x 64 tiles, which give that width
+  // only 64 workgroups).  Wide outputs keep the 64 x 64 tiles for few rows: with 192
+  // column tiles they already stream the weights at 5 TB/s.
+  if (m <= kSkinnyRows && p.n < kSkinnyMaxN) {
+    if (m <= 16) skinny_tile<8, 1>(p, m, smem, threadIdx.x); else skinny_tile<8, 2>(p, m, smem, threadIdx.x);
+    return;
+  }
   if (p.n % 256 == 0 && tiles_of(m, p.n, 256, 256) >= 2 * kWideSingle) {
     gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x);
   } else if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
@@ -504,17 +488,6 @@ hipError_t launch_fixed(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_rows(const GemmArgs& g, hipStream_t s) {
-  // worst case over the shapes the kernel may pick
-  const int small = 4 * ((g.n + 63) / 64);                           // <= 256 rows, 64 x 64
-  const int large = ((g.m_max + 127) / 128) * ((g.n + 127) / 128);  // 128 x 128
-  const int tiles = g.m_max <= 256 ? ((g.m_max + 63) / 64) * ((g.n + 63) / 64)
-                                   : (small > large ? small : large);
-  if (tiles == 0) return hipSuccess;
-  hipLaunchKernelGGL(gemm_bf16_rows_kernel, dim3(grid_for(tiles)), dim3(256), 0, s, to_dev(g));
-  return hipGetLastError();
-}
-
 hipError_t launch_rows_wide(const GemmArgs& g, hipStream_t s) {
   // worst case over the row counts 1 .. m_max of the blocks any of the shapes needs;
   // the 64 x 64 shape is only chosen below kWideBigTiles 128 x 128 tiles, each of which
@@ -549,11 +522,10 @@ hipError_t launch_gemm_bf16_cfg(const GemmArgs& g, int cfg, hipStream_t s) {
     case 12: return launch_fixed<64, 64, 2, 2, 4>(g, s);
     case 13: return launch_fixed<128, 128, 4, 2, 4>(g, s);
     case 14: return launch_fixed<128, 256, 2, 4, 2>(g, s);
-    case 20: return launch_rows(g, s);
     case 21: return launch_rows_wide(g, s);
     default: break;
   }
-  if (g.m_dev) return g.n >= 8192 ? launch_rows_wide(g, s) : launch_rows(g, s);
+  if (g.m_dev) return launch_rows_wide(g, s);
   // Row count known on the host.  Measured on MI355X (256 CUs): 256 x 256 tiles have
   // the least LDS-fill traffic per flop and win once they fill the chip; 256 x 192
   // gives exactly 256 tiles for 1024 x 12288; 128 x 128 with 8 waves is the best
