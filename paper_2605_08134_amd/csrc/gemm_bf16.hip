@@ -409,6 +409,8 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDe
 // operand tiles out of L2 (measured 45-80 GB/s per CU whatever the ring depth), so the
 // shape that wins moves the fewest bytes per CU while still using every CU:
 //   256 x 256 and 256 x 192 (the all-row shapes) once they fill the chip;
+//   128 x 192 (four waves) when that gives one round of 192-256 tiles (257-512 rows of a
+//   12288-wide output: 63 us against 72-79 us for 128 x 128 tiles, which need a second round);
 //   128 x 128 (4 x 2 waves, 4 stages) once that gives at least kWideBigTiles tiles;
 //   else 64 x 64 tiles, one per workgroup while there are at most kWideSingle of them
 //   (the other four waves end at once; waves that have ended do not count at a
@@ -418,9 +420,12 @@ constexpr int kWideBigTiles = 160, kWideSingle = 256, kWideFullTiles = 200;
 __host__ __device__ inline int tiles_of(int m, int n, int bm, int bn) {
   return ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
 }
+// a tile count that fills most of the chip's 256 CUs in a single round
+__host__ __device__ inline bool one_round(int tiles) { return tiles >= 192 && tiles <= 256; }
 __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kWideSmem];
-  static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem,
+  static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem &&
+                    smem_bytes<128, 192, 3>() <= kWideSmem,
                 "shared buffer too small");
   const int m = p.m_dev ? *p.m_dev : p.m_max;
   if (m <= 0) return;
@@ -436,6 +441,9 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
     gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x);
   } else if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
     gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x);
+  } else if (p.n % 192 == 0 && one_round(tiles_of(m, p.n, 128, 192))) {
+    if (threadIdx.x >= 256) return;  // four waves, 64 x 96 each
+    gemm_tile<128, 192, 2, 2, 3>(p, m, smem, threadIdx.x);
   } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
     gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x);
   } else {
