@@ -237,8 +237,10 @@ def main():
     features = model = None
     if not args.quick:
         features = feature_legs(torch, B, synth, wdev, weights, seed, xa, xb, Bn, T, d, H, Dh, tau, ms_dense)
+        features["layer_step_8x2048"] = step_at_c2(torch, B, synth, wdev, seed, tau)
         if args.model_steps > 0:
             model = model_leg(torch, B, np, dev, args.model_steps)
+            model["prefix_parallel"] = model_leg_prefix_parallel(torch, B, np, dev, max(4, args.model_steps // 4))
 
     # ---- CPU oracle on the host cores (reported baseline, not a target) ----------------------
     cpu = None
@@ -332,6 +334,85 @@ def feature_legs(torch, B, synth, wdev, weights, seed, xa, xb, Bn, T, d, H, Dh, 
                                           "dense_with_prefix_vs_dense": us_pd / (ms_dense * 1e3)}
     layer.destroy()
     return res
+
+
+def step_at_c2(torch, B, synth, wdev, seed, tau):
+    """The whole layer step at 8 sequences of 2048 tokens, per-sequence perturbed fraction
+    drawn in [5 %, 30 %] (the variable-row-count workload), KV+O against dense."""
+    c = synth.CONFIGS["llada8b_b8"]
+    Bn, T, d, H = c["batch"], c["seq"], c["hidden"], c["n_heads"]
+    dev = wdev[0].device
+    h = synth.make_hidden_pair(seed + 2, Bn, T, d, c["fraction"], "bf16")
+    xa = torch.from_numpy(h["x_prev"]).to(torch.bfloat16).to(dev)
+    xb = torch.from_numpy(h["x_cur"]).to(torch.bfloat16).to(dev)
+    layer = B.DareLayer(*wdev, n_heads=H, max_batch=Bn, max_seq=T)
+    mask = torch.zeros((Bn, T), dtype=torch.uint8, device=dev)
+    st = layer.new_state(Bn, T)
+    call = lambda mode, x: layer.layer_step(mode, tau, x, st["q_prev"], st["k_cache"], st["v_cache"],
+                                            st["o_cache"], st["o_cache"], mask)
+    call(B.MODE_DENSE, xa)
+    res = {}
+    for name, mode in (("kvo", B.MODE_KVO), ("dense", B.MODE_DENSE)):
+        res[name + "_us"] = _time_us(torch, lambda n, mode=mode: [call(mode, xb if i % 2 == 0 else xa)
+                                                                  for i in range(n)], 20, warm=4)
+        if mode == B.MODE_KVO:
+            res["reuse"] = float(mask.float().mean().item())
+    res["latency_vs_dense"] = res["kvo_us"] / res["dense_us"]
+    res["tokens_per_s_kvo"] = Bn * T / (res["kvo_us"] * 1e-6)
+    layer.destroy()
+    return res
+
+
+def model_leg_prefix_parallel(torch, B, np, dev, n_steps):
+    """The model leg with prefix caching and parallel unmasking: 4 sequences of 4096 tokens
+    (2048 prompt + 2048 mask ids), the prompt frozen after the first step, 4 positions of the
+    current block unmasked per step.  Three runs of the same schedule: all layers dense without
+    the frozen prefix, dense with it, KV+O reuse with it."""
+    L, d, H, ffn, V, Bn, T, P = 32, 4096, 32, 12288, 126464, 4, 4096, 2048
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20260509)
+    rn = lambda *shape, std=0.02: (torch.randn(shape, device=dev, generator=gen) * std).to(torch.bfloat16)
+    gain = lambda: (1.0 + 0.1 * torch.randn((d,), device=dev, generator=gen)).to(torch.bfloat16)
+    m = B.DareModel(L, d, H, ffn, V, Bn, T, B.DARE_BF16, 1e-5, 10000.0)
+    for l in range(L):
+        m.set_layer(l, gain(), rn(d, d), rn(d, d), rn(d, d), rn(d, d), gain(), rn(d, ffn), rn(d, ffn), rn(ffn, d))
+    m.set_io(rn(V, d, std=1.0), gain(), None)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.PCG64(20260509))
+    mask_id = V - 1
+    ids0 = np.full((Bn, T), mask_id, dtype=np.int32)
+    ids0[:, :P] = rng.integers(0, mask_id, (Bn, P))
+    order = np.stack([np.concatenate([b0 + rng.permutation(32) for b0 in range(P, T, 32)]) for _ in range(Bn)])
+    refreshed = torch.zeros((L, Bn), dtype=torch.int32, device=dev)
+    out = {}
+    for name, mode, thr, prefix in (("dense_no_prefix", B.MODE_DENSE, 0.0, 0), ("dense_prefix", B.MODE_DENSE, 0.0, P),
+                                    ("kvo_prefix", B.MODE_KVO, 1e-3, P)):
+        ids = torch.from_numpy(ids0.copy()).to(dev)
+        m.set_prefix(0)
+        m.step(B.MODE_DENSE, 0.0, ids)               # fills every layer's caches, prompt included
+        m.set_prefix(prefix)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        counts = []
+        e0.record()
+        for t in range(n_steps):
+            for b in range(Bn):
+                ids[b, torch.from_numpy(order[b, 4 * t:4 * t + 4]).to(dev)] = int(rng.integers(0, mask_id))
+            m.step(mode, thr, ids, None, refreshed)
+            counts.append(refreshed.clone())
+        e1.record()
+        torch.cuda.synchronize()
+        ref = torch.stack(counts).float().cpu().numpy()                   # [steps, layers, batch]
+        out[name] = {"step_us_mean": e0.elapsed_time(e1) * 1e3 / n_steps,
+                     "layer_us_mean": e0.elapsed_time(e1) * 1e3 / n_steps / L,
+                     "refreshed_per_sequence_mean": float(ref.mean()),
+                     "reuse_of_unfrozen_mean": float(1.0 - ref.mean() / (T - prefix))}
+    out["prefix_vs_no_prefix"] = out["dense_prefix"]["layer_us_mean"] / out["dense_no_prefix"]["layer_us_mean"]
+    out["reuse_and_prefix_vs_prefix"] = out["kvo_prefix"]["layer_us_mean"] / out["dense_prefix"]["layer_us_mean"]
+    out["config"] = {"layers": L, "batch": Bn, "seq": T, "prompt_frozen": P, "unmasked_per_step": 4, "block": 32,
+                     "steps_timed": n_steps, "threshold": 1e-3}
+    m.destroy()
+    return out
 
 
 def model_leg(torch, B, np, dev, n_steps):
