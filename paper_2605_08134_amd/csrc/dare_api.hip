@@ -642,8 +642,8 @@ dare_status dare_drift_stats_enable(dare_ctx* ctx, int on, void* hip_stream) {
     dare_status st = ensure_threshold_buffers(ctx);
     if (st != DARE_OK) return st;
     // ordered on the stream after the steps already enqueued
-    e = hipMemsetAsync(ctx->stat_sum, 0, 2 * sizeof(double), static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipMemsetAsync");
+    e = launch_zero_words(ctx->stat_sum, 2, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(ctx, e, "statistics reset");
   }
   ctx->stats_on = on != 0;
   return DARE_OK;

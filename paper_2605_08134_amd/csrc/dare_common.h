@@ -87,6 +87,7 @@ hipError_t launch_compact(const uint8_t* mask, int batch, int seq, int32_t* sel_
 hipError_t launch_quantile_mask(const float* scores, int batch, int stride, int first, int seq, int rank,
                                 int force_refresh, float* tau_out, uint8_t* mask, double* stat_sum,
                                 unsigned long long* stat_count, hipStream_t s);
+hipError_t launch_zero_words(void* p, int n, hipStream_t s);
 hipError_t launch_active_list(int batch, int seq, int prefix, int32_t* act_idx, int32_t* act_off, hipStream_t s);
 hipError_t launch_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops, hipStream_t s);
 hipError_t launch_copy_rows(const void* src, void* dst, int n_rows, int row_bytes,

@@ -344,6 +344,20 @@ hipError_t launch_quantile_mask(const float* scores, int batch, int stride, int 
   return hipGetLastError();
 }
 
+namespace {
+__global__ void zero_words_kernel(unsigned long long* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0ull;
+}
+}  // namespace
+
+// n 64-bit words <- 0 with a kernel (a memset node does not survive a graph capture)
+hipError_t launch_zero_words(void* p, int n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(zero_words_kernel, dim3((n + 63) / 64), dim3(64), 0, s, static_cast<unsigned long long*>(p), n);
+  return hipGetLastError();
+}
+
 hipError_t launch_active_list(int batch, int seq, int prefix, int32_t* act_idx, int32_t* act_off, hipStream_t s) {
   const long n = (long)batch * (seq - prefix);
   const int grid = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
