@@ -22,7 +22,8 @@
 // (max, sum, O) and are merged once at the end through LDS, in a fixed order.
 // Few query rows (the refreshed rows of a step) use narrow query blocks with KW > 1,
 // which turns the available waves towards the key axis and fills the chip; many
-// rows use wide blocks, which re-read K and V less often.
+// rows use wide blocks (128 rows with two key-waves, or 256 rows with none when there are
+// enough of them), which re-read K and V less often.
 #include <cstdlib>
 
 #include "dare_common.h"
@@ -352,6 +353,7 @@ hipError_t launch_dh(const AttnDev& p, const AttnArgs& a, int cfg, hipStream_t s
     case 5: return launch_variant<DH, 4, 2, 64, 2>(p, a, s);
     case 6: return launch_variant<DH, 2, 4, 32, 2>(p, a, s);
     case 7: return launch_variant<DH, 4, 2, 32, 4>(p, a, s);
+    case 8: return launch_variant<DH, 8, 1, 64, 2>(p, a, s);
     default: break;
   }
   // measured on MI355X: 8 waves per block.  Full rows take the wide block (128 rows, 2
@@ -359,6 +361,12 @@ hipError_t launch_dh(const AttnDev& p, const AttnArgs& a, int cfg, hipStream_t s
   // the narrow block (64 rows, 4 key-waves) is what fills the chip; with many pairs
   // the wide block already does and re-reads K and V less.
   if (a.idx && !a.many_rows && a.batch * a.n_heads < 128) return launch_variant<DH, 2, 4, 32, 2>(p, a, s);
+  // Most rows of every sequence and enough of them for a block of 256 query rows per
+  // workgroup (8 query-waves, no key split) to fill the chip: a K/V tile then feeds twice
+  // the MFMAs per byte that enters LDS (8 x 2048 tokens: 600-650 us against 750-880;
+  // 2 x 1024: 43 against 52 us; with 1 x 1024 tokens there are only 128 such blocks).
+  if ((!a.idx || a.many_rows) && (long)a.batch * a.n_heads * ((a.seq + 255) / 256) >= 256)
+    return launch_variant<DH, 8, 1, 64, 2>(p, a, s);
   return launch_variant<DH, 4, 2, 64, 2>(p, a, s);
 }
 

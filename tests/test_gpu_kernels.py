@@ -195,6 +195,7 @@ def _attn_case(seed, batch, seq, heads, dh, dtype, frac):
 @pytest.mark.parametrize("dtype,batch,seq,heads,dh", [
     ("bf16", 1, 256, 2, 128), ("bf16", 2, 200, 3, 128), ("bf16", 1, 1, 1, 128),
     ("bf16", 2, 333, 2, 64), ("bf16", 1, 65, 1, 64),
+    ("bf16", 8, 300, 16, 128), ("bf16", 4, 520, 32, 64),    # enough rows for the 256-row query blocks
     ("f32", 1, 128, 4, 64), ("f32", 2, 77, 2, 128), ("f32", 1, 1100, 1, 64),
 ])
 def test_attention_all_rows(B, dtype, batch, seq, heads, dh):
