@@ -134,8 +134,8 @@ def test_small_model_blockwise_steps(Bm, dtype):
     m.destroy()
 
 
-def test_small_model_prefix_and_quantile_rule(Bm):
-    dtype = "f32"
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_model_prefix_and_quantile_rule(Bm, dtype):
     cfg = dict(L=2, d=128, H=2, ffn=256, V=192, B=2, T=40)
     params = synth.make_model_params(6, cfg["L"], cfg["d"], cfg["ffn"], cfg["V"], dtype, with_head=False)
     m = _build(Bm, params, cfg, dtype)
