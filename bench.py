@@ -463,6 +463,41 @@ def model_leg(torch, B, np, dev, n_steps):
                      "reuse_mean": float(1.0 - ref.mean() / T),
                      "reuse_by_layer_first_mid_last": [float(1.0 - ref[:, l].mean() / T) for l in (0, L // 2, L - 1)]}
     out["layer_latency_vs_dense"] = out["kvo"]["layer_us_mean"] / out["dense"]["layer_us_mean"]
+
+    # Layer-wise reuse rates as the paper sets them (Sec. 3.1): mean drift per layer over a few
+    # calibration steps, phi_l = L phi_bar softmax(-s_l / eps) with the paper's phi_bar = 0.3, then
+    # the quantile rule with each layer's own rate.
+    ids = torch.from_numpy(ids0.copy()).to(dev)
+    m.step(B.MODE_DENSE, 0.0, ids)
+    for l in range(L):
+        m.layer(l).drift_stats_enable(True)
+    n_cal = min(8, n_steps)
+    for t in range(n_cal):
+        ids[0, order[t]] = int(new_ids[t])
+        m.step(B.MODE_DENSE, 0.0, ids)
+    s_layers = [m.layer(l).drift_stats_read()[0] for l in range(L)]
+    for l in range(L):
+        m.layer(l).drift_stats_enable(False)
+    eps = max(float(np.std(s_layers)), 1e-9)
+    phis = B.dare_allocate_quantiles(s_layers, 0.3, eps)
+    m.set_rule(B.RULE_QUANTILE)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    counts = []
+    n_q = max(4, n_steps // 4)
+    ev[0].record()
+    for t in range(n_cal, n_cal + n_q):
+        ids[0, order[t]] = int(new_ids[t])
+        m.step(B.MODE_KVO, phis, ids, None, refreshed)
+        counts.append(refreshed.clone())
+    ev[1].record()
+    torch.cuda.synchronize()
+    m.set_rule(B.RULE_SCORE)
+    ref = torch.stack(counts).float().cpu().numpy()[:, :, 0]
+    out["quantile_allocation"] = {
+        "phi_bar": 0.3, "eps": eps, "mean_drift_first_mid_last": [s_layers[0], s_layers[L // 2], s_layers[-1]],
+        "phi_min_max": [float(min(phis)), float(max(phis))], "phi_mean": float(np.mean(phis)),
+        "reuse_mean": float(1.0 - ref.mean() / T), "layer_us_mean": ev[0].elapsed_time(ev[1]) * 1e3 / n_q / L,
+        "vs_dense": ev[0].elapsed_time(ev[1]) * 1e3 / n_q / L / out["dense"]["layer_us_mean"]}
     out["config"] = {"layers": L, "hidden": d, "heads": H, "ffn": ffn, "vocab": V, "seq": T, "prompt": P,
                      "block": 32, "steps_timed": n_steps, "threshold": 1e-3,
                      "note": "per-layer latency includes the layer's feed-forward, which DARE does not touch"}
