@@ -189,6 +189,10 @@ def main():
     host_kvo = host_ms[B.MODE_KVO]
     ms_dense, _, _, _ = time_mode(B.MODE_DENSE, xa, xb, max(20, args.steps // 4), args.warmup)
 
+    graph = None
+    if not args.quick:
+        graph = graph_replay(torch, layer, B, xa, xb, Bn, T, tau, mask, fill)
+
     latency = None
     if not args.quick:
         latency = {"kvo_us": latency_distribution(B.MODE_KVO, xa, xb, 200),
@@ -270,6 +274,7 @@ def main():
         "roofline_other": roofline_other,
         "measured_peaks": peaks,
         "latency": latency,
+        "graph_replay": graph,
         "cold_weights": cold,
         "features": features,
         "model": model,
@@ -277,6 +282,31 @@ def main():
         "sweep": sweep,
     }
     print(json.dumps(out))
+
+
+def graph_replay(torch, layer, B, xa, xb, Bn, T, tau, mask, fill):
+    """The same steps captured once into a HIP graph (8 steps per graph) and replayed: what the
+    launches cost when the host is out of the loop."""
+    res = {}
+    for name, mode in (("kvo_us", B.MODE_KVO), ("dense_us", B.MODE_DENSE)):
+        st = layer.new_state(Bn, T)
+        fill(st, xa)
+        side = torch.cuda.Stream()
+        call = lambda x: layer.layer_step(mode, tau, x, st["q_prev"], st["k_cache"], st["v_cache"], st["o_cache"],
+                                          st["o_cache"], mask)
+        with torch.cuda.stream(side):
+            call(xb)
+            call(xa)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(4):
+                call(xb)
+                call(xa)
+        torch.cuda.synchronize()
+        res[name] = _time_us(torch, lambda n: [g.replay() for _ in range(n)], 25, warm=3) / 8
+    res["latency_vs_dense"] = res["kvo_us"] / res["dense_us"]
+    return res
 
 
 def _time_us(torch, fn, iters, warm=3):
