@@ -208,3 +208,31 @@ def test_llada8b_batch8_variable_rows():
                                          np.full(case["seq"] - n_b, -1, dtype=np.int32)])
         sub["sel_count"] = got["sel_count"][b:b + 1]
         pu.check_step(sub, want, st, orc.MODE_KVO, tau, "bf16")
+
+
+# ------------------------------------------------------------------ whole-query scoring (score_head = -1)
+@pytest.mark.parametrize("name,shape", [("tiny", {}), ("llada8b", dict(batch=2, seq=150, hidden=256, n_heads=2, head_dim=128))])
+@pytest.mark.parametrize("mode", MODES)
+def test_score_over_the_whole_query(name, shape, mode):
+    """Sec. 3.1 defines the drift on the whole query; Sec. 3.2 takes head 0.  score_head = -1 selects
+    the former: the score cache is [B, T, hidden] and the scored columns are all of Q."""
+    from paper_2605_08134_amd import binding as B
+    case = synth.make_case(name, seed=31, **shape)
+    dt = case["dtype"]
+    out, Q, K, V = orc.dense_layer(case["x_prev"], case["wq"], case["wk"], case["wv"], case["wo"], case["n_heads"])
+    state = {"q_prev": np.asarray(Q, dtype=np.float32), "k_cache": pu.store(K, dt), "v_cache": pu.store(V, dt),
+             "o_cache": pu.store(out, dt)}
+    gl = pu.GpuLayer.__new__(pu.GpuLayer)
+    gl.B, gl.case, gl.dt = B, case, dt
+    gl.layer = B.DareLayer(*[pu.dev(case[k], dt) for k in ("wq", "wk", "wv", "wo")], n_heads=case["n_heads"],
+                           max_batch=case["batch"], max_seq=case["seq"], score_head=-1)
+    storage = "bf16" if dt == "bf16" else None
+    run = lambda tau: orc.layer_step(mode, tau, case["x_cur"], case["wq"], case["wk"], case["wv"], case["wo"],
+                                     state["q_prev"], state["k_cache"], state["v_cache"], state["o_cache"],
+                                     case["n_heads"], score_head=-1, storage=storage)
+    s = run(0.0)["scores"]
+    for tau in (-1.0, pu.gap_threshold(s, 0.7), 2.5):
+        got = gl.step(mode, tau, case["x_cur"], state)
+        pu.check_step(got, run(tau), state, mode, tau, dt)
+        assert got["q_prev"].shape[-1] == case["hidden"]
+    gl.layer.destroy()
