@@ -96,14 +96,19 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk,
  *                     be the same pointer as o_cache (then no copy is made);
  *                     partial overlap is an error the call cannot detect.
  *   reuse_mask out    [batch, seq] bytes, 1 = reused, 0 = refreshed (all 0 in
- *                     DENSE)
+ *                     DENSE; always 1 for the tokens of a frozen prefix, see
+ *                     dare_set_prefix)
  *   sel_idx    out, optional (NULL to skip) [batch*seq] int32: ascending flat
  *                     token ids b*seq+i of the refreshed tokens; entries past
  *                     the total count are left as they were
  *   sel_count  out, optional [batch] int32: refreshed tokens per sequence
  *   scores     out, optional [batch, seq] fp32 drift scores
  *   threshold  compared in fp32, reuse iff score <= threshold; ignored in DENSE.
- *              A NaN score refreshes.  NaN threshold is INVALID_ARG.
+ *              A NaN score refreshes.  NaN threshold is INVALID_ARG.  Under
+ *              DARE_RULE_QUANTILE (dare_set_threshold_rule) it is a reuse rate.
+ *
+ * The call enqueues kernels only (no allocation, no memset, no host synchronisation), so
+ * it may be recorded into a HIP graph.
  *
  * Errors: INVALID_ARG (null required pointer, unknown mode, batch or seq < 1,
  * batch > max_batch, seq > max_seq, NaN threshold), HIP (a launch failed).

@@ -106,7 +106,7 @@ hipError_t attn(const dare_ctx* c, const AttnArgs& a, hipStream_t s) {
 
 extern "C" {
 
-const char* dare_version(void) { return "0.1"; }
+const char* dare_version(void) { return "0.2"; }
 
 const char* dare_last_error(const dare_ctx* ctx) {
   return ctx ? ctx->err.c_str() : g_create_err.c_str();
