@@ -309,6 +309,23 @@ def graph_replay(torch, layer, B, xa, xb, Bn, T, tau, mask, fill):
     return res
 
 
+def _time_graph_us(torch, call, reps=20, iters=20):
+    """Per-launch time of a short kernel: `reps` launches captured into one HIP graph and the
+    graph replayed, so that the figure is the kernel's and not the host's enqueue rate
+    (a ctypes call costs about 8 us, more than these kernels take).  call(stream) enqueues one
+    launch on the given stream."""
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        call(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for _ in range(reps):
+            call(side)
+    torch.cuda.synchronize()
+    return _time_us(torch, lambda n: [g.replay() for _ in range(n)], iters, warm=2) / reps
+
+
 def _time_us(torch, fn, iters, warm=3):
     fn(warm)
     torch.cuda.synchronize()
@@ -607,8 +624,7 @@ def other_kernels_at_c2(torch, B, np, dev, d, H, Dh):
     q_prev = rnd(n_tok, Dh)
     scores = torch.empty(n_tok, dtype=torch.float32, device=dev)
     mask = torch.empty(n_tok, dtype=torch.uint8, device=dev)
-    us = _time_us(torch, lambda n: [B.dare_k_score(q_new, q_prev, 5e-3, False, scores, mask)
-                                    for _ in range(n)], 50)
+    us = _time_graph_us(torch, lambda st: B.dare_k_score(q_new, q_prev, 5e-3, False, scores, mask, stream=st))
     nbytes = n_tok * (3 * Dh * 4 + 5)
     out.append({"kernel": "score_kernel (%d tokens)" % n_tok, "bound": "hbm",
                 "achieved": nbytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -618,8 +634,7 @@ def other_kernels_at_c2(torch, B, np, dev, d, H, Dh):
     sel_idx = torch.empty(n_tok, dtype=torch.int32, device=dev)
     sel_count = torch.empty(Bn, dtype=torch.int32, device=dev)
     sel_off = torch.empty(Bn + 1, dtype=torch.int32, device=dev)
-    us = _time_us(torch, lambda n: [B.dare_k_compact(mask, Bn, T, sel_idx, sel_count, sel_off)
-                                    for _ in range(n)], 50)
+    us = _time_graph_us(torch, lambda st: B.dare_k_compact(mask, Bn, T, sel_idx, sel_count, sel_off, stream=st))
     n_sel = int(sel_off[-1].item())
     nbytes = n_tok + 4 * n_sel
     out.append({"kernel": "compact_kernel (%d tokens, %d refreshed)" % (n_tok, n_sel), "bound": "hbm",
@@ -630,8 +645,7 @@ def other_kernels_at_c2(torch, B, np, dev, d, H, Dh):
     src = rnd(n_tok, d).to(torch.bfloat16)
     dst = torch.empty_like(src)
     m_dev = sel_off[-1:].clone()
-    us = _time_us(torch, lambda n: [B.dare_k_copy_rows(src, dst, idx=sel_idx, m_dev=m_dev)
-                                    for _ in range(n)], 50)
+    us = _time_graph_us(torch, lambda st: B.dare_k_copy_rows(src, dst, idx=sel_idx, m_dev=m_dev, stream=st))
     nbytes = 2 * n_sel * d * 2
     out.append({"kernel": "copy_rows_kernel (%d rows of 8 KiB)" % n_sel, "bound": "hbm",
                 "achieved": nbytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -60,14 +60,30 @@ __global__ void __launch_bounds__(256) score_kernel(const float* __restrict__ q_
   const float* q = q_new + (long)tok * ld_new;
   float* p = q_prev + (long)tok * width;
   float dot = 0.f, nq = 0.f, np = 0.f;
-  for (int c = lane; c < width; c += 64) {
-    float a = q[c];
-    for (int s = 1; s < n_parts; ++s) a += q[c + s * part_stride];  // k-range slabs, in order
-    const float b = p[c];
-    dot = fmaf(a, b, dot);
-    nq = fmaf(a, a, nq);
-    np = fmaf(b, b, np);
-    p[c] = a;  // the score cache takes this step's query for every token
+  if ((width & 1) == 0 && (ld_new & 1) == 0 && (part_stride & 1) == 0) {
+    // two neighbouring channels per lane: 8-byte loads, all slabs of a pair in flight at once
+    for (int c = lane * 2; c < width; c += 128) {
+      f32x2 a = *reinterpret_cast<const f32x2*>(q + c);
+      for (int s = 1; s < n_parts; ++s) a += *reinterpret_cast<const f32x2*>(q + c + s * part_stride);  // k-range slabs, in order
+      const f32x2 b = *reinterpret_cast<const f32x2*>(p + c);
+      dot = fmaf(a[0], b[0], dot);
+      nq = fmaf(a[0], a[0], nq);
+      np = fmaf(b[0], b[0], np);
+      dot = fmaf(a[1], b[1], dot);
+      nq = fmaf(a[1], a[1], nq);
+      np = fmaf(b[1], b[1], np);
+      *reinterpret_cast<f32x2*>(p + c) = a;  // the score cache takes this step's query for every token
+    }
+  } else {
+    for (int c = lane; c < width; c += 64) {
+      float a = q[c];
+      for (int s = 1; s < n_parts; ++s) a += q[c + s * part_stride];
+      const float b = p[c];
+      dot = fmaf(a, b, dot);
+      nq = fmaf(a, a, nq);
+      np = fmaf(b, b, np);
+      p[c] = a;
+    }
   }
   dot = wave_sum(dot);
   nq = wave_sum(nq);
@@ -100,9 +116,25 @@ __device__ inline int block_sum_256(int v, int* sh) {
   return sh[0] + sh[1] + sh[2] + sh[3];
 }
 
+// refreshed tokens (mask byte 0; the bytes are 0 or 1) in [begin, end), summed over the
+// workgroup's threads by the caller: 16 bytes per thread and step between the aligned
+// bounds, single bytes at the ragged ends
 __device__ inline int count_refreshed(const uint8_t* __restrict__ mask, long begin, long end) {
   int c = 0;
-  for (long i = begin + threadIdx.x; i < end; i += 256) c += mask[i] == 0;
+  const long a0 = (begin + 15) & ~15l, a1 = end & ~15l;
+  if (a0 >= a1) {
+    for (long i = begin + threadIdx.x; i < end; i += 256) c += mask[i] == 0;
+    return c;
+  }
+  for (long i = begin + threadIdx.x; i < a0; i += 256) c += mask[i] == 0;
+  for (long i = a1 + threadIdx.x; i < end; i += 256) c += mask[i] == 0;
+  const u32x4* v = reinterpret_cast<const u32x4*>(mask + a0);
+  const long nv = (a1 - a0) >> 4;
+  for (long i = threadIdx.x; i < nv; i += 256) {
+    const u32x4 w = v[i];
+    c += 16 - __popc(w[0] & 0x01010101u) - __popc(w[1] & 0x01010101u) - __popc(w[2] & 0x01010101u) -
+         __popc(w[3] & 0x01010101u);
+  }
   return c;
 }
 

@@ -165,7 +165,8 @@ def test_score_kernel(B):
 
 
 @pytest.mark.parametrize("batch,seq,frac", [(1, 128, 0.2), (3, 1000, 0.5), (2, 2500, 0.07),
-                                            (4, 64, 0.0), (2, 1024, 1.0), (8, 2048, 0.2)])
+                                            (4, 64, 0.0), (2, 1024, 1.0), (8, 2048, 0.2),
+                                            (3, 1031, 0.3), (5, 7, 0.5), (2, 4099, 0.9)])   # sequence starts off the 16-byte grid
 def test_compaction_is_ordered_and_exact(B, batch, seq, frac):
     r = _rng(batch * seq)
     reuse = r.random((batch, seq)) >= frac
