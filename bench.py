@@ -714,7 +714,7 @@ def cpu_baseline(weights, seed, cfg, tau):
     xs = (h["x_cur"], h["x_prev"])
     t0 = time.perf_counter()
     n = 0
-    while n < 2 or (time.perf_counter() - t0 < 10.0 and n < 50):
+    while n < 2 or (time.perf_counter() - t0 < 12.0 and n < 400):
         r = orc.layer_step(orc.MODE_KVO, tau, xs[n % 2], w["wq"], w["wk"], w["wv"], w["wo"],
                            st["q_prev"], st["k_cache"], st["v_cache"], st["o_cache"], H)
         st = {k: r[k] for k in st}
