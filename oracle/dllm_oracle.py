@@ -14,9 +14,10 @@ something to be checked against:
 
 with RMS normalisation (gain only), rotary embedding on Q and K, no biases, weights
 [d_in, d_out].  silu(z) = z / (1 + exp(-z)).  Numpy float64 throughout; with
-storage="bf16" every tensor named above (the normalised rows, gate, up, their product,
-the feed-forward output, each residual sum, y) is rounded to bfloat16 where it is
-produced, as in dare_oracle.
+storage="bf16" every tensor that is stored (the normalised rows, the gated product
+silu(n W_g) * (n W_u), the feed-forward output, each residual sum, y) is rounded to
+bfloat16 where it is produced, as in dare_oracle; the gate and up projections themselves
+are not stored tensors (they are consumed where they are produced) and are not rounded.
 
 The decoding schedule (``blockwise_schedule``) is the block-wise one the paper uses
 (block size 32, Sec. 5 / App. A): the generated region is filled block by block, left
@@ -48,8 +49,8 @@ def ffn_block(x, gain, eps, w_gate, w_up, w_down, storage=None, rows=None):
     x = np.asarray(x, dtype=np.float64)
     rs = orc.round_storage
     n = rs(orc.rms_norm(x, gain, eps), storage)
-    g = rs(n @ np.asarray(w_gate, dtype=np.float64), storage)
-    u = rs(n @ np.asarray(w_up, dtype=np.float64), storage)
+    g = n @ np.asarray(w_gate, dtype=np.float64)
+    u = n @ np.asarray(w_up, dtype=np.float64)
     a = rs(silu(g) * u, storage)
     f = rs(a @ np.asarray(w_down, dtype=np.float64), storage)
     exact = x + f

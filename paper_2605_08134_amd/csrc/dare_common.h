@@ -42,6 +42,10 @@ struct GemmArgs {
   // of (cos, sin) pairs; position of a row = token id % rope_seq); nullptr = none
   const float* rope;
   int rope_cols, rope_dh, rope_seq;
+  // 1: the output columns are (gate, up) pairs of a SwiGLU feed-forward (weight rows
+  // interleaved gate_0, up_0, gate_1, ...): column pair (2j, 2j+1) gives one output
+  // silu(gate_j) * up_j at column j of c[0] (bf16 path, one segment, no c32)
+  int swiglu_pairs;
 };
 
 // Rotation of the channel pairs (v0, v1) and (v2, v3) of four neighbouring output

@@ -64,6 +64,7 @@ struct GemmDev {
   long c32_part_stride;  // elements between the fp32 outputs of consecutive ranges
   const float* rope;     // rotary table, or nullptr
   int rope_cols, rope_dh, rope_seq;
+  int swiglu_pairs;
 };
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -95,6 +96,13 @@ constexpr int smem_bytes() {
 // store into the column's segment.
 __device__ __forceinline__ void store4(const GemmDev& p, float* c32, long tok, int col, float v0, float v1,
                                        float v2, float v3) {
+  if (p.swiglu_pairs) {  // (gate, up) pairs: two outputs silu(gate) * up at columns col / 2, col / 2 + 1
+    bf16x2 o;
+    o[0] = (bf16_t)(v0 / (1.0f + __expf(-v0)) * v1);
+    o[1] = (bf16_t)(v2 / (1.0f + __expf(-v2)) * v3);
+    *reinterpret_cast<bf16x2*>(p.c0 + tok * p.ldc + (col >> 1)) = o;
+    return;
+  }
   if (c32 && col < p.c32_cols) {
     const f32x4 o = {v0, v1, v2, v3};
     *reinterpret_cast<f32x4*>(c32 + tok * p.c32_cols + col) = o;
@@ -477,6 +485,7 @@ GemmDev to_dev(const GemmArgs& g) {
   p.rope_cols = g.rope_cols;
   p.rope_dh = g.rope_dh;
   p.rope_seq = g.rope_seq;
+  p.swiglu_pairs = g.swiglu_pairs;
   return p;
 }
 

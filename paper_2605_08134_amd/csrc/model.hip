@@ -295,9 +295,17 @@ dare_status dare_model_set_layer(dare_model* m, int layer, const void* attn_gain
     return mfail(m, st, std::string("layer settings: ") + dare_last_error(ctx));
   const size_t es = m->esize, d = c.hidden, ff = c.ffn;
   e = hipMemcpyAsync(lm.ffn_gain, ffn_gain, d * es, hipMemcpyDeviceToDevice, s);
-  if (e == hipSuccess) e = launch_pack_weight(c.dtype, w_gate, c.hidden, c.ffn, lm.w_gu_t, c.hidden, s);
-  if (e == hipSuccess)
-    e = launch_pack_weight(c.dtype, w_up, c.hidden, c.ffn, static_cast<char*>(lm.w_gu_t) + ff * d * es, c.hidden, s);
+  if (c.dtype == DARE_BF16) {
+    // gate and up rows interleaved (gate_0, up_0, gate_1, ...): the projection's epilogue
+    // then holds each (gate, up) pair in one lane and applies the SwiGLU gate itself
+    if (e == hipSuccess) e = launch_pack_weight(c.dtype, w_gate, c.hidden, c.ffn, lm.w_gu_t, 2 * c.hidden, s);
+    if (e == hipSuccess)
+      e = launch_pack_weight(c.dtype, w_up, c.hidden, c.ffn, static_cast<char*>(lm.w_gu_t) + d * es, 2 * c.hidden, s);
+  } else {
+    if (e == hipSuccess) e = launch_pack_weight(c.dtype, w_gate, c.hidden, c.ffn, lm.w_gu_t, c.hidden, s);
+    if (e == hipSuccess)
+      e = launch_pack_weight(c.dtype, w_up, c.hidden, c.ffn, static_cast<char*>(lm.w_gu_t) + ff * d * es, c.hidden, s);
+  }
   if (e == hipSuccess) e = launch_pack_weight(c.dtype, w_down, c.ffn, c.hidden, lm.w_down_t, c.ffn, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e != hipSuccess) return mfail_hip(m, e, "feed-forward weights");
@@ -407,13 +415,19 @@ dare_status dare_model_step(dare_model* m, const int32_t* modes, const float* th
     g.m_max = n_act;
     g.idx = act;
     g.c[0] = m->gate;
-    g.c[1] = m->up;
     g.ldc = ff;
-    g.seg_n = ff;
     g.k_parts = 1;
-    e = c.dtype == DARE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+    if (c.dtype == DARE_BF16) {
+      g.seg_n = 2 * ff;
+      g.swiglu_pairs = 1;  // silu(gate) * up leaves the epilogue; gate and up are never stored
+      e = launch_gemm_bf16(g, s);
+    } else {
+      g.c[1] = m->up;
+      g.seg_n = ff;
+      e = launch_gemm_f32(g, s);
+      if (e == hipSuccess) e = launch_swiglu(c.dtype, m->gate, m->up, n_act, ff, act, s);
+    }
     if (e != hipSuccess) return mfail_hip(m, e, "gate / up projection");
-    if ((e = launch_swiglu(c.dtype, m->gate, m->up, n_act, ff, act, s)) != hipSuccess) return mfail_hip(m, e, "swiglu");
     GemmArgs h{};
     h.a = m->gate;
     h.lda = ff;
