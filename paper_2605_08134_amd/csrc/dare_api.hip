@@ -519,6 +519,25 @@ dare_status dare_block_step(dare_ctx* ctx, int mode, float threshold, int batch,
                    reuse_mask, sel_idx, sel_count, scores, bx, hip_stream);
 }
 
+}  // extern "C"
+
+namespace dare {
+dare_status block_core(dare_ctx* ctx, int mode, float threshold, int batch, int seq, const void* h, float* q_prev,
+                       void* k_cache, void* v_cache, void* o_cache, uint8_t* reuse_mask, int32_t* sel_count,
+                       void* hip_stream) {
+  if (!ctx) return DARE_ERR_INVALID_ARG;
+  if (!ctx->has_block) return fail(ctx, DARE_ERR_INVALID_ARG, "no block attached");
+  dare_status st = check_step_args(ctx, mode, threshold, batch, seq, h, q_prev, k_cache, v_cache, o_cache,
+                                   o_cache, reuse_mask);
+  if (st != DARE_OK) return st;
+  BlockExtras bx{ctx->block.rope_base > 0.f ? ctx->rope_table : nullptr, nullptr};
+  return step_impl(ctx, mode, threshold, batch, seq, h, q_prev, k_cache, v_cache, o_cache, o_cache, reuse_mask,
+                   nullptr, sel_count, nullptr, bx, hip_stream);
+}
+}  // namespace dare
+
+extern "C" {
+
 // ---------------------------------------------------------------------------
 // kernel-level entry points
 // ---------------------------------------------------------------------------

@@ -101,11 +101,21 @@ hipError_t launch_norm(int dtype, int kind, const void* x, const void* gain, con
                        int n_rows, int d, void* out, int seq, int prefix, hipStream_t s);
 hipError_t launch_residual_add(int dtype, const void* x, const void* o, void* out, long n_elems,
                                hipStream_t s);
+hipError_t launch_residual_norm(int dtype, void* x, const void* o, const void* gain, float eps, int n_rows, int d,
+                                void* h, int seq, int prefix, hipStream_t s);
 hipError_t launch_residual_rows(int dtype, void* x, const void* f, int n_rows, int d, const int32_t* idx,
                                 hipStream_t s);
 hipError_t launch_gather_rows(const void* src, void* dst, const int32_t* ids, int n_rows, int n_src,
                               int row_bytes, hipStream_t s);
 hipError_t launch_swiglu(int dtype, void* gate, const void* up, int n_rows, int width, const int32_t* idx,
                          hipStream_t s);
+
+// The attention block of dare_block_step without its first and last launch, for the model
+// runtime, which fuses them with its neighbours: `h` is the hidden state already normalised,
+// the block output O goes into o_cache only (no residual sum).  Arguments are checked as
+// in dare_layer_step; rotary embedding as attached to the context.
+dare_status block_core(dare_ctx* ctx, int mode, float threshold, int batch, int seq, const void* h, float* q_prev,
+                       void* k_cache, void* v_cache, void* o_cache, uint8_t* reuse_mask, int32_t* sel_count,
+                       void* hip_stream);
 
 }  // namespace dare

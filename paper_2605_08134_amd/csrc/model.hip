@@ -99,6 +99,7 @@ struct dare_model {
   void* final_gain;
   void* head_t;       // [vocab, hidden] packed output embedding, or nullptr
   void* x;            // [max tokens, hidden] residual stream
+  void* h1;           // normalised rows feeding the attention block
   void* h2;           // normalised rows feeding the feed-forward
   void* gate;         // [max tokens, ffn]
   void* up;
@@ -204,6 +205,7 @@ dare_status dare_model_create(const dare_model_config* cfg, void* hip_stream, da
   const size_t d = cfg->hidden, es = m->esize, tok = (size_t)max_tok;
   struct { void** p; size_t bytes; bool zero; } bufs[] = {
       {&m->x, tok * d * es, false},          {&m->h2, tok * d * es, false},
+      {&m->h1, tok * d * es, false},
       {&m->gate, tok * cfg->ffn * es, false}, {&m->up, tok * cfg->ffn * es, false},
       {&m->f, tok * d * es, false},          {&m->rows_buf, tok * d * es, false},
       {(void**)&m->mask, tok, false},        {(void**)&m->act_idx, tok * sizeof(int32_t), false},
@@ -295,6 +297,7 @@ dare_status dare_model_set_layer(dare_model* m, int layer, const void* attn_gain
     return mfail(m, st, std::string("layer settings: ") + dare_last_error(ctx));
   const size_t es = m->esize, d = c.hidden, ff = c.ffn;
   e = hipMemcpyAsync(lm.ffn_gain, ffn_gain, d * es, hipMemcpyDeviceToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(lm.attn_gain, attn_gain, d * es, hipMemcpyDeviceToDevice, s);
   if (c.dtype == DARE_BF16) {
     // gate and up rows interleaved (gate_0, up_0, gate_1, ...): the projection's epilogue
     // then holds each (gate, up) pair in one lane and applies the SwiGLU gate itself
@@ -394,18 +397,26 @@ dare_status dare_model_step(dare_model* m, const int32_t* modes, const float* th
 
   if ((e = launch_gather_rows(m->embed, m->x, ids, n_tok, c.vocab, (int)(d * es), s)) != hipSuccess)
     return mfail_hip(m, e, "embedding");
+  // Every residual sum is fused with the normalisation that follows it (one pass over the
+  // stream instead of two): x <- x + O, n = rmsnorm(x) before the feed-forward; x <- x + F,
+  // h = rmsnorm(x) before the next layer's attention.  Only the first normalisation and the
+  // last sum stand alone.
+  e = launch_norm(c.dtype, DARE_NORM_RMS, m->x, m->mem[0].attn_gain, nullptr, c.norm_eps, n_act, d, m->h1,
+                  pre ? seq : 0, P, s);
+  if (e != hipSuccess) return mfail_hip(m, e, "first norm");
   for (int l = 0; l < c.n_layers; ++l) {
     dare_model::LayerMem& lm = m->mem[l];
     if ((e = snapshot(2 * l)) != hipSuccess) return mfail_hip(m, e, "trace");
-    // attention block: x <- x + O(rmsnorm(x)), in place (the residual sum is its last launch)
-    dare_status st = dare_block_step(m->layers[l], modes[l], thresholds[l], batch, seq, m->x, lm.q_prev, lm.k_cache,
-                                     lm.v_cache, lm.o_cache, m->x, m->mask, nullptr,
-                                     refreshed ? refreshed + (size_t)l * batch : nullptr, nullptr, hip_stream);
+    // attention block on the normalised rows; its output O goes to the layer's output cache
+    dare_status st = block_core(m->layers[l], modes[l], thresholds[l], batch, seq, m->h1, lm.q_prev, lm.k_cache,
+                                lm.v_cache, lm.o_cache, m->mask, refreshed ? refreshed + (size_t)l * batch : nullptr,
+                                hip_stream);
     if (st != DARE_OK) return mfail(m, st, "layer " + std::to_string(l) + ": " + dare_last_error(m->layers[l]));
+    // x <- x + O for every row (frozen rows add their cached O), n = rmsnorm(x)
+    e = launch_residual_norm(c.dtype, m->x, lm.o_cache, lm.ffn_gain, c.norm_eps, n_tok, d, m->h2, 0, 0, s);
+    if (e != hipSuccess) return mfail_hip(m, e, "attention residual + feed-forward norm");
     if ((e = snapshot(2 * l + 1)) != hipSuccess) return mfail_hip(m, e, "trace");
-    // feed-forward on the rows that are not frozen: x <- x + (silu(n Wg) * (n Wu)) Wd
-    e = launch_norm(c.dtype, DARE_NORM_RMS, m->x, lm.ffn_gain, nullptr, c.norm_eps, n_act, d, m->h2, pre ? seq : 0, P, s);
-    if (e != hipSuccess) return mfail_hip(m, e, "feed-forward norm");
+    // feed-forward on the rows that are not frozen: F = (silu(n Wg) * (n Wu)) Wd
     GemmArgs g{};
     g.a = m->h2;
     g.lda = d;
@@ -442,8 +453,11 @@ dare_status dare_model_step(dare_model* m, const int32_t* modes, const float* th
     h.k_parts = 1;
     e = c.dtype == DARE_BF16 ? launch_gemm_bf16(h, s) : launch_gemm_f32(h, s);
     if (e != hipSuccess) return mfail_hip(m, e, "down projection");
-    if (pre) {
-      // frozen rows of f were never written: add row by row over the active rows only
+    if (l + 1 < c.n_layers) {
+      // x <- x + F on the rows that are not frozen, h = rmsnorm(x) for the next layer
+      e = launch_residual_norm(c.dtype, m->x, m->f, m->mem[l + 1].attn_gain, c.norm_eps, n_act, d, m->h1,
+                               pre ? seq : 0, P, s);
+    } else if (pre) {
       e = launch_residual_rows(c.dtype, m->x, m->f, n_act, d, act, s);
     } else {
       e = launch_residual_add(c.dtype, m->x, m->f, m->x, (long)n_tok * d, s);

@@ -140,6 +140,54 @@ __global__ void __launch_bounds__(256) residual_add_kernel(const T* __restrict__
   }
 }
 
+// x[t, :] <- x[t, :] + o[t, :] (rounded to T as it is stored), h[t, :] <- that row / sqrt(mean of its
+// squares + eps) * gain: the residual sum of one block fused with the RMS normalisation that opens
+// the next.  One workgroup per row, the row held in registers (d <= 256 * 8 * kHold), rows mapped
+// past a frozen prefix as in norm_kernel.
+template <typename T>
+__global__ void __launch_bounds__(256) residual_norm_kernel(T* __restrict__ x, const T* __restrict__ o,
+                                                            const T* __restrict__ gain, float eps, int d,
+                                                            T* __restrict__ h, int seq, int prefix) {
+  __shared__ float sh[4];
+  long tok = blockIdx.x;
+  if (seq > 0) tok = (tok / (seq - prefix)) * seq + prefix + tok % (seq - prefix);
+  T* xr = x + tok * d;
+  const T* orow = o + tok * d;
+  T* hr = h + tok * d;
+  const int groups = d >> 3;
+  float v[kHold][8];
+  float s1 = 0.f;
+#pragma unroll
+  for (int k = 0; k < kHold; ++k) {
+    const int g = threadIdx.x + k * 256;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[k][e] = 0.f;
+    if (g < groups) {
+      float a[8], b[8];
+      load8(xr + g * 8, a);
+      load8(orow + g * 8, b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[k][e] = (float)(T)(a[e] + b[e]);  // the stored sum
+      store8(xr + g * 8, v[k]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s1 += v[k][e] * v[k][e];
+  }
+  s1 = block_sum(s1, sh);
+  const float scale = 1.0f / sqrtf(s1 / (float)d + eps);
+#pragma unroll
+  for (int k = 0; k < kHold; ++k) {
+    const int g = threadIdx.x + k * 256;
+    if (g < groups) {
+      float gn[8], y[8];
+      load8(gain + g * 8, gn);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) y[e] = v[k][e] * scale * gn[e];
+      store8(hr + g * 8, y);
+    }
+  }
+}
+
 // x[t, :] += f[t, :] for the listed rows (a frozen prefix leaves the other rows alone).
 template <typename T>
 __global__ void __launch_bounds__(256) residual_rows_kernel(T* __restrict__ x, const T* __restrict__ f, int n_rows,
@@ -159,6 +207,22 @@ __global__ void __launch_bounds__(256) residual_rows_kernel(T* __restrict__ x, c
 }
 
 }  // namespace
+
+// returns hipErrorInvalidValue for rows longer than the kernel holds in registers
+hipError_t launch_residual_norm(int dtype, void* x, const void* o, const void* gain, float eps, int n_rows, int d,
+                                void* h, int seq, int prefix, hipStream_t s) {
+  if (n_rows == 0) return hipSuccess;
+  if (d > 256 * 8 * kHold || (d & 7)) return hipErrorInvalidValue;
+  if (dtype == DARE_BF16)
+    hipLaunchKernelGGL(residual_norm_kernel<bf16_t>, dim3(n_rows), dim3(256), 0, s, static_cast<bf16_t*>(x),
+                       static_cast<const bf16_t*>(o), static_cast<const bf16_t*>(gain), eps, d,
+                       static_cast<bf16_t*>(h), seq, prefix);
+  else
+    hipLaunchKernelGGL(residual_norm_kernel<float>, dim3(n_rows), dim3(256), 0, s, static_cast<float*>(x),
+                       static_cast<const float*>(o), static_cast<const float*>(gain), eps, d, static_cast<float*>(h),
+                       seq, prefix);
+  return hipGetLastError();
+}
 
 hipError_t launch_residual_rows(int dtype, void* x, const void* f, int n_rows, int d, const int32_t* idx,
                                 hipStream_t s) {
