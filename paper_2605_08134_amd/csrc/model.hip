@@ -85,7 +85,7 @@ struct dare_model {
   size_t esize;
   std::vector<dare_ctx*> layers;
   struct LayerMem {
-    void* attn_gain;  // kept until the layer's context is created
+    void* attn_gain;  // gains of the two normalisations (the fused residual + norm kernels read them)
     void* ffn_gain;
     void* w_gu_t;     // [2 ffn, hidden] packed gate | up
     void* w_down_t;   // [hidden, ffn] packed
