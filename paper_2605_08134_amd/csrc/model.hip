@@ -1,8 +1,10 @@
 // A masked-diffusion language model made of DARE layers: host-side runtime (buffers,
 // per-layer contexts, the launch sequence of one denoising step) plus the two small
 // kernels the model adds to the layer's: row gather (token embedding, rows for the
-// output embedding) and the SwiGLU gate.  The attention of every layer is
-// dare_block_step; the feed-forward uses the projection kernels of the layer.
+// output embedding) and the SwiGLU gate of the fp32 path (the bf16 path applies it in the
+// epilogue of the gate/up projection).  The attention of every layer is the core of
+// dare_block_step, with its normalisation and residual sum fused into the model's own
+// residual + norm passes; the feed-forward uses the projection kernels of the layer.
 #include <cmath>
 #include <new>
 #include <string>
