@@ -318,8 +318,11 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
     if (e != hipSuccess) return fail_hip(ctx, e, "threshold selection");
   }
 
-  // 3. Index list of the refreshed tokens.
-  if (mode != DARE_MODE_DENSE || sel_idx || sel_count) {
+  // 3. Index list of the refreshed tokens.  With at most kSelMaxTokens tokens the bf16
+  //    refreshed-row projection derives the list itself (and leaves it for the kernels after
+  //    it): one launch less.
+  const bool fused_sel = sel_kv && cf.dtype == DARE_BF16 && n_tok <= kSelMaxTokens;
+  if (!fused_sel && (mode != DARE_MODE_DENSE || sel_idx || sel_count)) {
     e = launch_compact(reuse_mask, batch, seq, ctx->sel_idx, sel_idx, sel_count, nullptr,
                        ctx->sel_off, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "compaction");
@@ -333,8 +336,18 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
     r.lda = d;
     r.k = d;
     r.m_max = n_tok;
-    r.idx = ctx->sel_idx;
-    r.m_dev = n_sel;
+    if (fused_sel) {
+      r.sel_mask = reuse_mask;
+      r.sel_batch = batch;
+      r.sel_seq = seq;
+      r.sel_idx_out = ctx->sel_idx;
+      r.sel_idx_out2 = sel_idx;
+      r.sel_off_out = ctx->sel_off;
+      r.sel_count_out = sel_count;
+    } else {
+      r.idx = ctx->sel_idx;
+      r.m_dev = n_sel;
+    }
     r.ldc = d;
     r.seg_n = d;
     r.rope = bx.rope;

@@ -46,7 +46,19 @@ struct GemmArgs {
   // interleaved gate_0, up_0, gate_1, ...): column pair (2j, 2j+1) gives one output
   // silu(gate_j) * up_j at column j of c[0] (bf16 path, one segment, no c32)
   int swiglu_pairs;
+  // Row list derived inside the kernel (bf16, device-count kernel only; replaces idx and
+  // m_dev): the rows are the tokens whose byte in sel_mask [sel_batch * sel_seq] is 0, in
+  // ascending order.  The first workgroup also writes what a compaction kernel would:
+  // sel_idx_out (and optionally sel_idx_out2) [tokens], sel_off_out [sel_batch + 1],
+  // optionally sel_count_out [sel_batch].  At most kSelMaxTokens tokens.
+  const uint8_t* sel_mask;
+  int sel_batch, sel_seq;
+  int32_t* sel_idx_out;
+  int32_t* sel_idx_out2;
+  int32_t* sel_off_out;
+  int32_t* sel_count_out;
 };
+constexpr int kSelMaxTokens = 2048;
 
 // Rotation of the channel pairs (v0, v1) and (v2, v3) of four neighbouring output
 // columns col .. col + 3 (col a multiple of 4) of token tok.

@@ -65,10 +65,23 @@ struct GemmDev {
   const float* rope;     // rotary table, or nullptr
   int rope_cols, rope_dh, rope_seq;
   int swiglu_pairs;
+  const uint8_t* sel_mask;
+  int sel_batch, sel_seq;
+  int32_t* sel_idx_out;
+  int32_t* sel_idx_out2;
+  int32_t* sel_off_out;
+  int32_t* sel_count_out;
 };
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
+typedef const __attribute__((address_space(3))) int32_t* lds_idx_t;  // a row list held in LDS
+
+// Token id of listed row `row`: from the list in LDS when the kernel derived it itself, else
+// from the caller's list, else the row itself.
+__device__ __forceinline__ long row_token(const int32_t* __restrict__ gidx, lds_idx_t lidx, int row) {
+  return lidx ? (long)lidx[row] : (gidx ? (long)gidx[row] : (long)row);
+}
 
 // Wait until at most N of this wave's vector-memory operations are outstanding
 // and all of its LDS reads have returned, then join the workgroup barrier.
@@ -126,7 +139,8 @@ __device__ __forceinline__ void store4(const GemmDev& p, float* c32, long tok, i
 // team without a tile of its own repeats the last tile and stores nothing.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigned char* smem,
-                                          const int tid, const int sub = 0, const int nsub = 1) {
+                                          const int tid, const int sub = 0, const int nsub = 1,
+                                          lds_idx_t lidx = nullptr) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -181,7 +195,7 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
     if (r < BM) {
       int row = m0 + r;
       row = row < m ? row : m - 1;
-      const long tok = p.idx ? (long)p.idx[row] : (long)row;
+      const long tok = row_token(p.idx, lidx, row);
       src[i] = p.a + tok * p.lda + chunk * 8 + kt0 * BK;
     } else {
       int col = n0 + (r - BM);
@@ -189,6 +203,15 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
       src[i] = p.wt + (long)col * p.k + chunk * 8 + kt0 * BK;
     }
   }
+  // token ids of the rows this lane stores in the epilogue, read now: a list held in LDS
+  // (lidx) sits in the stage memory that the first loads overwrite
+  long tok_out[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wave_m * WM + i * 32 + l32;
+    tok_out[i] = row_token(p.idx, lidx, row < m ? row : m - 1);
+  }
+  if (lidx) __syncthreads();  // (uniform: every thread of the workgroup has its entries)
   auto issue_loads = [&](int kt, int buf) __attribute__((always_inline)) {
     unsigned char* base = smem + buf * STAGE_BYTES + wave * LPW * 8 * ROW_BYTES;
 #pragma unroll
@@ -317,7 +340,7 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + wave_m * WM + i * 32 + l32;
     if (row >= m || !live) continue;
-    const long tok = p.idx ? (long)p.idx[row] : (long)row;
+    const long tok = tok_out[i];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -341,7 +364,8 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
 // (weight fragment first, so a lane again owns one row and four neighbouring columns), and
 // the partial sums of the waves are added in wave order through LDS.
 template <int NW, int TMS>
-__device__ __forceinline__ void skinny_tile(const GemmDev& p, const int m, unsigned char* smem, const int tid) {
+__device__ __forceinline__ void skinny_tile(const GemmDev& p, const int m, unsigned char* smem, const int tid,
+                                            lds_idx_t lidx = nullptr) {
   constexpr int UNR = TMS == 1 ? 16 : 8;
   const int lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, kq = lane >> 4;
@@ -356,9 +380,10 @@ __device__ __forceinline__ void skinny_tile(const GemmDev& p, const int m, unsig
   for (int t = 0; t < TMS; ++t) {
     int r = t * 16 + l16;
     r = r < m ? r : m - 1;
-    tok[t] = p.idx ? (long)p.idx[r] : (long)r;
+    tok[t] = row_token(p.idx, lidx, r);
     xrow[t] = p.a + tok[t] * p.lda + kq * 8;
   }
+  if (lidx) __syncthreads();  // a list in LDS shares the memory of the partial sums below
   f32x4* red = reinterpret_cast<f32x4*>(smem);  // [NW][TMS][64]
   for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
     const int n0 = grp << 4;
@@ -430,35 +455,108 @@ __host__ __device__ inline int tiles_of(int m, int n, int bm, int bn) {
 }
 // a tile count that fills most of the chip's 256 CUs in a single round
 __host__ __device__ inline bool one_round(int tiles) { return tiles >= 192 && tiles <= 256; }
+// The refreshed-row list from the mask bytes, by every workgroup for itself (Alg. 1/2 line 5
+// folded into the first kernel that needs the list: a compaction kernel of its own costs a
+// launch, 4-5 us of a 90 us step, for a few hundred bytes of work).  512 threads, up to
+// kSelMaxTokens tokens, four per thread; ascending by construction.  Returns the count.
+__device__ __forceinline__ int derive_rows(const GemmDev& p, int32_t* list, int* wave_tot) {
+  const int n_tok = p.sel_batch * p.sel_seq;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t0 = tid * 4;
+  bool z[4];
+  int cnt = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    z[k] = t0 + k < n_tok && p.sel_mask[t0 + k] == 0;
+    cnt += z[k];
+  }
+  int incl = cnt;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  int rank = incl - cnt, total = 0;
+#pragma unroll
+  for (int w = 0; w < 8; ++w) {
+    if (w < wave) rank += wave_tot[w];
+    total += wave_tot[w];
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (z[k]) list[rank++] = t0 + k;
+  __syncthreads();
+  if (blockIdx.x == 0) {  // what the compaction kernel would have written, for the kernels that follow
+    for (int r = tid; r < total; r += 512) {
+      p.sel_idx_out[r] = list[r];
+      if (p.sel_idx_out2) p.sel_idx_out2[r] = list[r];
+    }
+    if (tid <= p.sel_batch) {
+      // refreshed tokens in front of sequence tid: first list position holding a token >= tid * seq
+      auto before = [&](int b) {
+        const int key = b * p.sel_seq;
+        int lo = 0, hi = total;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (list[mid] < key) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+      };
+      const int off = before(tid);
+      p.sel_off_out[tid] = off;
+      if (p.sel_count_out && tid < p.sel_batch) p.sel_count_out[tid] = before(tid + 1) - off;
+    }
+  }
+  return total;
+}
+
 __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kWideSmem];
+  // a row list derived from the mask lives at the start of the stage memory until every
+  // thread has taken the entries it needs (gemm_tile / skinny_tile read them before their
+  // first load into LDS); a workgroup that allocates more than 128 KiB of LDS was measured
+  // 20 % slower on this chip, so the list gets no memory of its own
+  static_assert(kSelMaxTokens * 4 + 64 <= kWideSmem, "row list must fit the stage memory");
+  // (the list starts 64 bytes in: LDS offset 0 is the null pointer of the LDS address space,
+  // and gemm_tile takes "no list" as a null pointer)
+  int* sel_wave_tot = reinterpret_cast<int*>(smem);
+  int32_t* sel_list = reinterpret_cast<int32_t*>(smem + 64);
   static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem &&
                     smem_bytes<128, 192, 3>() <= kWideSmem,
                 "shared buffer too small");
-  const int m = p.m_dev ? *p.m_dev : p.m_max;
+  int m;
+  lds_idx_t lidx = nullptr;
+  if (p.sel_mask) {
+    m = derive_rows(p, sel_list, sel_wave_tot);
+    lidx = (lds_idx_t)sel_list;
+  } else {
+    m = p.m_dev ? *p.m_dev : p.m_max;
+  }
   if (m <= 0) return;
   // Up to 32 rows and a narrow output (the output projection): the register-fed stream
   // (measured at n = 4096: 11-15 us against 17 us for 64 x 64 tiles, which give that width
   // only 64 workgroups).  Wide outputs keep the 64 x 64 tiles for few rows: with 192
   // column tiles they already stream the weights at 5 TB/s.
   if (m <= kSkinnyRows && p.n < kSkinnyMaxN) {
-    if (m <= 16) skinny_tile<8, 1>(p, m, smem, threadIdx.x); else skinny_tile<8, 2>(p, m, smem, threadIdx.x);
+    if (m <= 16) skinny_tile<8, 1>(p, m, smem, threadIdx.x, lidx); else skinny_tile<8, 2>(p, m, smem, threadIdx.x, lidx);
     return;
   }
   if (p.n % 256 == 0 && tiles_of(m, p.n, 256, 256) >= 2 * kWideSingle) {
-    gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x);
+    gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x, 0, 1, lidx);
   } else if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
-    gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x);
+    gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x, 0, 1, lidx);
   } else if (p.n % 192 == 0 && one_round(tiles_of(m, p.n, 128, 192))) {
     if (threadIdx.x >= 256) return;  // four waves, 64 x 96 each
-    gemm_tile<128, 192, 2, 2, 3>(p, m, smem, threadIdx.x);
+    gemm_tile<128, 192, 2, 2, 3>(p, m, smem, threadIdx.x, 0, 1, lidx);
   } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
-    gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x);
+    gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x, 0, 1, lidx);
   } else {
     const int team = threadIdx.x >> 8;
     const int teams = tiles_of(m, p.n, 64, 64) > kWideSingle ? 2 : 1;
     if (team >= teams) return;
-    gemm_tile<64, 64, 2, 2, 4>(p, m, smem + team * smem_bytes<64, 64, 4>(), threadIdx.x & 255, team, teams);
+    gemm_tile<64, 64, 2, 2, 4>(p, m, smem + team * smem_bytes<64, 64, 4>(), threadIdx.x & 255, team, teams, lidx);
   }
 }
 
@@ -486,6 +584,13 @@ GemmDev to_dev(const GemmArgs& g) {
   p.rope_dh = g.rope_dh;
   p.rope_seq = g.rope_seq;
   p.swiglu_pairs = g.swiglu_pairs;
+  p.sel_mask = g.sel_mask;
+  p.sel_batch = g.sel_batch;
+  p.sel_seq = g.sel_seq;
+  p.sel_idx_out = g.sel_idx_out;
+  p.sel_idx_out2 = g.sel_idx_out2;
+  p.sel_off_out = g.sel_off_out;
+  p.sel_count_out = g.sel_count_out;
   return p;
 }
 
@@ -542,7 +647,7 @@ hipError_t launch_gemm_bf16_cfg(const GemmArgs& g, int cfg, hipStream_t s) {
     case 21: return launch_rows_wide(g, s);
     default: break;
   }
-  if (g.m_dev) return launch_rows_wide(g, s);
+  if (g.m_dev || g.sel_mask) return launch_rows_wide(g, s);
   // Row count known on the host.  Measured on MI355X (256 CUs): 256 x 256 tiles have
   // the least LDS-fill traffic per flop and win once they fill the chip; 256 x 192
   // gives exactly 256 tiles for 1024 x 12288; 128 x 128 with 8 waves is the best
