@@ -354,6 +354,152 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   }
 }
 
+// The same tile with v_mfma_f32_16x16x32_bf16: wave tiles in units of 16, so that 8 waves can
+// share a 128 x 96 tile (32 x 48 each).  129-256 refreshed rows of a 12288-wide output then
+// make 256 workgroups of 8 waves, where the 32-wide MFMA shape allows either 192 workgroups
+// (128 x 128) or 4 waves per workgroup (128 x 96 as 32 x 96).  LDS layout, ring and loads as in
+// gemm_tile; a fragment is 16 rows x 32 k (lane L: row L & 15, k-chunk L >> 4), a k-step holds
+// two such slices, and all fragments of the next k-step are fetched under the MFMAs of the
+// current one.  No teams, no k-parts.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+__device__ __forceinline__ void gemm_tile16(const GemmDev& p, const int m, unsigned char* smem, const int tid,
+                                            lds_idx_t lidx = nullptr) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 16, TN = WN / 16;
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  constexpr int GROUPS = (BM + BN) / 8;
+  constexpr int LPW = (GROUPS + NW - 1) / NW;  // surplus loads repeat the last group
+  constexpr int KS = BK / 32;
+  static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be a multiple of 16 x 16");
+  static_assert(LPW * (STAGES - 1) < 64, "vmcnt range");
+
+  const int tiles_m = (m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) >> 3;
+  const int slot = blockIdx.x >> 3;
+  if (slot >= per_xcd) return;
+  const int unit = (blockIdx.x & 7) * per_xcd + slot;
+  if (unit >= total) return;
+  const int group_size = GROUP_M * tiles_n;
+  const int first_m = (unit / group_size) * GROUP_M;
+  const int rows_in_group = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+  const int rem = unit % group_size;
+  const int tile_m = first_m + rem % rows_in_group, tile_n = rem / rows_in_group;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int KT = p.k / BK;
+
+  const bf16_t* src[LPW];
+  int grp[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    grp[i] = wave * LPW + i < GROUPS ? wave * LPW + i : GROUPS - 1;
+    const int r = grp[i] * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+    if (r < BM) {
+      int row = m0 + r;
+      row = row < m ? row : m - 1;
+      src[i] = p.a + row_token(p.idx, lidx, row) * p.lda + chunk * 8;
+    } else {
+      int col = n0 + (r - BM);
+      col = col < p.n ? col : p.n - 1;
+      src[i] = p.wt + (long)col * p.k + chunk * 8;
+    }
+  }
+  long tok_out[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wave_m * WM + i * 16 + l16;
+    tok_out[i] = row_token(p.idx, lidx, row < m ? row : m - 1);
+  }
+  if (lidx) __syncthreads();
+  auto issue_loads = [&](int kt, int buf) __attribute__((always_inline)) {
+    unsigned char* base = smem + buf * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < LPW; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + kt * BK), (lptr_t)(base + grp[i] * 8 * ROW_BYTES), 16, 0, 0);
+  };
+
+  f32x4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // fragment offsets: row (base + 16 i + l16), chunk 4 ks + kq at slot chunk ^ ((row >> 1) & 7); the
+  // bases are multiples of 16, so the XOR term depends on l16 only
+  const int sw = (l16 >> 1) & 7;
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = ((ks * 4 + kq) ^ sw) * 16;
+  const int a_row_off = (wave_m * WM + l16) * ROW_BYTES;
+  const int b_row_off = (BM + wave_n * WN + l16) * ROW_BYTES;
+
+  bf16x8 fa[2][KS][TM], fb[2][KS][TN];
+  auto load_frags = [&](int buf, int set) __attribute__((always_inline)) {
+    const unsigned char* st = smem + buf * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        fa[set][ks][i] = *reinterpret_cast<const bf16x8*>(st + a_row_off + i * 16 * ROW_BYTES + koff[ks]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        fb[set][ks][j] = *reinterpret_cast<const bf16x8*>(st + b_row_off + j * 16 * ROW_BYTES + koff[ks]);
+    }
+  };
+  constexpr int NMMA = KS * TM * TN, PRE = 2;
+  auto mma = [&](int set, int first, int last) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < NMMA; ++t) {
+      if (t < first || t >= last) continue;
+      const int ks = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[set][ks][j], fa[set][ks][i], acc[i][j], 0, 0, 0);
+    }
+  };
+
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) issue_loads(s < KT ? s : KT - 1, s);
+  wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
+  load_frags(0, 0);
+  auto kstep = [&](int kt, auto set_c) __attribute__((always_inline)) {
+    constexpr int SET = decltype(set_c)::value;
+    const int nxt = kt + STAGES - 1;
+    issue_loads(nxt < KT ? nxt : KT - 1, nxt % STAGES);
+    mma(SET, 0, PRE);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
+    load_frags((kt + 1) % STAGES, SET ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(SET, PRE, NMMA);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
+    kstep(kt, std::integral_constant<int, 0>{});
+    kstep(kt + 1, std::integral_constant<int, 1>{});
+  }
+  if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
+  wait_vmcnt<0>();
+
+  // acc[i][j][e] = C[row, col]: row = m0 + wave_m*WM + 16 i + l16, col = n0 + wave_n*WN + 16 j + 4 kq + e
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wave_m * WM + i * 16 + l16;
+    if (row >= m) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wave_n * WN + j * 16 + kq * 4;
+      if (col >= p.n) continue;
+      store4(p, p.c32, tok_out[i], col, acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+    }
+  }
+}
+
 // ---- very few rows (at most 16 TMS): a stream over the weight matrix ------------------
 // With a handful of refreshed rows (one or two tokens unmasked per denoising step) the
 // projection is a matrix-vector product in disguise: what matters is that every CU pulls on
@@ -524,7 +670,7 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   int* sel_wave_tot = reinterpret_cast<int*>(smem);
   int32_t* sel_list = reinterpret_cast<int32_t*>(smem + 64);
   static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem &&
-                    smem_bytes<128, 192, 3>() <= kWideSmem,
+                    smem_bytes<128, 192, 3>() <= kWideSmem && smem_bytes<128, 96, 4>() <= kWideSmem,
                 "shared buffer too small");
   int m;
   lds_idx_t lidx = nullptr;
@@ -550,6 +696,8 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   } else if (p.n % 192 == 0 && one_round(tiles_of(m, p.n, 128, 192))) {
     if (threadIdx.x >= 256) return;  // four waves, 64 x 96 each
     gemm_tile<128, 192, 2, 2, 3>(p, m, smem, threadIdx.x, 0, 1, lidx);
+  } else if (p.n % 96 == 0 && one_round(tiles_of(m, p.n, 128, 96))) {
+    gemm_tile16<128, 96, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
   } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
     gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x, 0, 1, lidx);
   } else {
