@@ -591,9 +591,9 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDe
 //   128 x 192 (four waves) when that gives one round of 192-256 tiles (257-512 rows of a
 //   12288-wide output: 63 us against 72-79 us for 128 x 128 tiles, which need a second round);
 //   128 x 128 (4 x 2 waves, 4 stages) once that gives at least kWideBigTiles tiles;
-//   else 64 x 64 tiles, one per workgroup while there are at most kWideSingle of them
-//   (the other four waves end at once; waves that have ended do not count at a
-//   barrier), and two per workgroup, one per team of four waves, beyond that.
+//   else 64 x 64 tiles, one per workgroup (all eight waves, 16-wide MFMA shape) while
+//   there are at most kWideSingle of them, and two per workgroup, one per team of four
+//   waves, beyond that.
 constexpr int kWideSmem = smem_bytes<128, 128, 4>();
 constexpr int kWideBigTiles = 160, kWideSingle = 256, kWideFullTiles = 200;
 __host__ __device__ inline int tiles_of(int m, int n, int bm, int bn) {
@@ -670,7 +670,8 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   int* sel_wave_tot = reinterpret_cast<int*>(smem);
   int32_t* sel_list = reinterpret_cast<int32_t*>(smem + 64);
   static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem &&
-                    smem_bytes<128, 192, 3>() <= kWideSmem && smem_bytes<128, 96, 4>() <= kWideSmem,
+                    smem_bytes<128, 192, 3>() <= kWideSmem && smem_bytes<128, 96, 4>() <= kWideSmem &&
+                    smem_bytes<128, 48, 5>() <= kWideSmem,
                 "shared buffer too small");
   int m;
   lds_idx_t lidx = nullptr;
@@ -694,8 +695,9 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   } else if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
     gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x, 0, 1, lidx);
   } else if (p.n % 192 == 0 && one_round(tiles_of(m, p.n, 128, 192))) {
-    if (threadIdx.x >= 256) return;  // four waves, 64 x 96 each
-    gemm_tile<128, 192, 2, 2, 3>(p, m, smem, threadIdx.x, 0, 1, lidx);
+    gemm_tile16<128, 192, 4, 2, 3>(p, m, smem, threadIdx.x, lidx);
+  } else if (m > 64 && p.n % 48 == 0 && one_round(tiles_of(m, p.n, 128, 48))) {
+    gemm_tile16<128, 48, 8, 1, 5>(p, m, smem, threadIdx.x, lidx);
   } else if (p.n % 96 == 0 && one_round(tiles_of(m, p.n, 128, 96))) {
     gemm_tile16<128, 96, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
   } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
@@ -703,7 +705,12 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   } else {
     const int team = threadIdx.x >> 8;
     const int teams = tiles_of(m, p.n, 64, 64) > kWideSingle ? 2 : 1;
-    if (team >= teams) return;
+    if (teams == 1) {
+      // one tile per workgroup: all eight waves on it (16 x 32 each with the 16-wide MFMA
+      // shape; measured 19.2 against 21.1 us for four waves of 32 x 32 at 205 rows, n = 4096)
+      gemm_tile16<64, 64, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
+      return;
+    }
     gemm_tile<64, 64, 2, 2, 4>(p, m, smem + team * smem_bytes<64, 64, 4>(), threadIdx.x & 255, team, teams, lidx);
   }
 }
