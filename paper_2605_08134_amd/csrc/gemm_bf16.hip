@@ -671,7 +671,7 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   int32_t* sel_list = reinterpret_cast<int32_t*>(smem + 64);
   static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem &&
                     smem_bytes<128, 192, 3>() <= kWideSmem && smem_bytes<128, 96, 4>() <= kWideSmem &&
-                    smem_bytes<128, 48, 5>() <= kWideSmem,
+                    smem_bytes<128, 48, 5>() <= kWideSmem && smem_bytes<128, 64, 4>() <= kWideSmem,
                 "shared buffer too small");
   int m;
   lds_idx_t lidx = nullptr;
@@ -698,6 +698,9 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
     gemm_tile16<128, 192, 4, 2, 3>(p, m, smem, threadIdx.x, lidx);
   } else if (m > 64 && p.n % 48 == 0 && one_round(tiles_of(m, p.n, 128, 48))) {
     gemm_tile16<128, 48, 8, 1, 5>(p, m, smem, threadIdx.x, lidx);
+  } else if (m > 256 && one_round(tiles_of(m, p.n, 128, 64))) {
+    gemm_tile16<128, 64, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
+
   } else if (p.n % 96 == 0 && one_round(tiles_of(m, p.n, 128, 96))) {
     gemm_tile16<128, 96, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
   } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
