@@ -698,7 +698,7 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
     gemm_tile16<128, 192, 4, 2, 3>(p, m, smem, threadIdx.x, lidx);
   } else if (m > 64 && p.n % 48 == 0 && one_round(tiles_of(m, p.n, 128, 48))) {
     gemm_tile16<128, 48, 8, 1, 5>(p, m, smem, threadIdx.x, lidx);
-  } else if (m > 256 && one_round(tiles_of(m, p.n, 128, 64))) {
+  } else if (m > 128 && one_round(tiles_of(m, p.n, 128, 64))) {
     gemm_tile16<128, 64, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
 
   } else if (p.n % 96 == 0 && one_round(tiles_of(m, p.n, 128, 96))) {
