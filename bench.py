@@ -603,7 +603,7 @@ def measured_peaks(torch, B, dev, d):
 
         def run(n, pattern=pattern):
             for _ in range(n):
-                flops[0] = B.dare_k_calib_mfma(2048, 4096, pattern)
+                flops[0] = B.dare_bench_mfma_loop(2048, 4096, pattern)
         us = _time_us(torch, run, 5, warm=2)
         res[key] = flops[0] / (us * 1e-6) / 1e12
     return res

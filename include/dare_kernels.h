@@ -87,14 +87,11 @@ dare_status dare_k_compact(const uint8_t* mask, int batch, int seq,
  * Row set: all tokens when idx == NULL; else idx[sel_off[b] .. sel_off[b+1]) for
  * each sequence b (idx, sel_off as produced by dare_k_compact).
  *   q, k, v, out  [batch*seq, n_heads*head_dim] dtype, token-indexed rows
- *   work          scratch of work_bytes bytes (may be NULL/0: then the key range
- *                 is never split across workgroups)
  */
 dare_status dare_k_attention(int dtype, const void* q, const void* k,
                              const void* v, void* out, int batch, int seq,
                              int n_heads, int head_dim, const int32_t* idx,
-                             const int32_t* sel_off, void* work,
-                             uint64_t work_bytes, void* hip_stream);
+                             const int32_t* sel_off, void* hip_stream);
 
 /*
  * Row copy between token-indexed buffers: dst[t] = src[t] for t in idx[0..*m_dev)
@@ -112,8 +109,9 @@ dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows,
  * phi in [0, 1]: per sequence tau = k-th smallest score, k = ceil(phi * seq) in fp32;
  * writes tau_out[batch] (optional) and mask[batch, seq] = (score <= tau), all 0 when
  * force_refresh.  phi < 0: statistics only, mask and tau_out are not touched.
- * stat_sum / stat_count (both or neither): device accumulators to which the sum and the
- * number of the non-NaN scores are added atomically.
+ * stat_sum / stat_count (both or neither): device arrays of [batch] slots; the sum and the
+ * number of the non-NaN scores of sequence b are added to slot b (plain read-modify-write by
+ * the one workgroup that owns the sequence: no atomics, the same result from run to run).
  */
 dare_status dare_k_quantile_mask(const float* scores, int batch, int seq, float phi,
                                  int force_refresh, float* tau_out, uint8_t* mask,
@@ -152,18 +150,6 @@ dare_status dare_k_norm(int dtype, int kind, const void* x, const void* gain,
 /* Residual sum out = x + o over n_elems elements (a multiple of 8) of dtype. */
 dare_status dare_k_residual_add(int dtype, const void* x, const void* o, void* out,
                                 long n_elems, void* hip_stream);
-
-/*
- * Calibration of the matrix-core peak that the projection and attention kernels are
- * measured against (no paper passage: measurement aid).  Enqueues n_blocks workgroups
- * of 4 waves, each wave issuing n_iter * 8 v_mfma_f32_32x32x16_bf16 on registers only.
- * pattern 0: zero operands; 1: operands that differ per lane.  *flops (HOST pointer,
- * may be NULL) receives the flop count of the launch; out (device, may be NULL) is
- * never written in practice.  Time the launch with events: flops / time is what the
- * matrix pipes sustain.
- */
-dare_status dare_k_calib_mfma(int n_blocks, int n_iter, int pattern, float* out,
-                              double* flops, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,7 @@ MODE_NAMES = {MODE_DENSE: "dense", MODE_KV: "kv", MODE_O: "o", MODE_KVO: "kvo"}
 EXPORTS = (
     "dare_create", "dare_layer_step", "dare_destroy", "dare_last_error", "dare_version",
     "dare_k_pack_weight", "dare_k_gemm", "dare_k_score", "dare_k_compact",
-    "dare_k_attention", "dare_k_copy_rows", "dare_k_calib_mfma",
+    "dare_k_attention", "dare_k_copy_rows",
     "dare_block_attach", "dare_block_step", "dare_k_gemm_rope", "dare_k_rope_table",
     "dare_k_norm", "dare_k_residual_add",
     "dare_set_threshold_rule", "dare_get_thresholds", "dare_drift_stats_enable", "dare_drift_stats_read",
@@ -110,12 +110,10 @@ def lib():
     L.dare_k_score.restype = i32
     L.dare_k_compact.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     L.dare_k_compact.restype = i32
-    L.dare_k_attention.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, u64, vp]
+    L.dare_k_attention.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     L.dare_k_attention.restype = i32
     L.dare_k_copy_rows.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     L.dare_k_copy_rows.restype = i32
-    L.dare_k_calib_mfma.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
-    L.dare_k_calib_mfma.restype = i32
     L.dare_block_attach.argtypes = [vp, ctypes.POINTER(DareBlockConfig), vp, vp, vp]
     L.dare_block_attach.restype = i32
     L.dare_block_step.argtypes = [vp, i32, f32, i32, i32] + [vp] * 11
@@ -466,13 +464,11 @@ def dare_k_compact(mask, batch, seq, sel_idx, sel_count, sel_off, stream=None):
                                 _stream(stream)))
 
 
-def dare_k_attention(q, k, v, out, batch, seq, n_heads, head_dim, idx=None, sel_off=None, work=None,
-                     stream=None):
+def dare_k_attention(q, k, v, out, batch, seq, n_heads, head_dim, idx=None, sel_off=None, stream=None):
     import torch
     dtype = DARE_BF16 if q.dtype == torch.bfloat16 else DARE_F32
-    wb = 0 if work is None else work.numel() * work.element_size()
     _check(lib().dare_k_attention(dtype, _ptr(q), _ptr(k), _ptr(v), _ptr(out), batch, seq, n_heads,
-                                  head_dim, _ptr(idx), _ptr(sel_off), _ptr(work), wb, _stream(stream)))
+                                  head_dim, _ptr(idx), _ptr(sel_off), _stream(stream)))
 
 
 def dare_k_copy_rows(src, dst, idx=None, m_dev=None, stream=None):
@@ -482,8 +478,30 @@ def dare_k_copy_rows(src, dst, idx=None, m_dev=None, stream=None):
                                   _stream(stream)))
 
 
-def dare_k_calib_mfma(n_blocks, n_iter, pattern, stream=None):
+# ---- benchmark aids (libdare_bench.so, include/dare_bench.h) ------------------------------
+
+BENCH_LIB_PATH = os.path.join(PKG_DIR, "libdare_bench.so")
+BENCH_EXPORTS = ("dare_bench_mfma_loop",)
+_bench_lib = None
+
+
+def bench_lib():
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(BENCH_LIB_PATH):
+            raise RuntimeError("libdare_bench.so is not built: run `python -m paper_2605_08134_amd.build`")
+        L = ctypes.CDLL(BENCH_LIB_PATH)
+        L.dare_bench_mfma_loop.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double),
+                                                                ctypes.c_void_p]
+        L.dare_bench_mfma_loop.restype = ctypes.c_int
+        _bench_lib = L
+    return _bench_lib
+
+
+def dare_bench_mfma_loop(n_blocks, n_iter, pattern, stream=None):
     """Enqueue the register-resident MFMA loop; returns the flop count of the launch."""
     flops = ctypes.c_double(0.0)
-    _check(lib().dare_k_calib_mfma(n_blocks, n_iter, pattern, None, ctypes.byref(flops), _stream(stream)))
+    st = bench_lib().dare_bench_mfma_loop(n_blocks, n_iter, pattern, None, ctypes.byref(flops), _stream(stream))
+    if st != 0:
+        raise DareError(st, "dare_bench_mfma_loop failed")
     return flops.value

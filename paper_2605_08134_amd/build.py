@@ -11,6 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libdare.so")
+BENCH_LIB_PATH = os.path.join(PKG_DIR, "libdare_bench.so")   # benchmark aids, csrc/bench/
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON_FLAGS = [
@@ -23,22 +24,25 @@ COMMON_FLAGS = [
 
 
 def sources():
-    return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
+    """The product library's sources, then (under bench/) those of the benchmark aids."""
+    return (sorted(f for f in os.listdir(CSRC) if f.endswith(".hip")) +
+            sorted(os.path.join("bench", f) for f in os.listdir(os.path.join(CSRC, "bench")) if f.endswith(".hip")))
 
 
 def _compile(src):
-    obj = os.path.join(OBJ_DIR, src[:-4] + ".o")
+    obj = os.path.join(OBJ_DIR, src[:-4].replace(os.sep, "_") + ".o")
     cmd = [HIPCC] + COMMON_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     return src, obj, r
 
 
 def build_library(verbose=True):
-    """Compile every .hip source for gfx950 and link libdare.so.  Always recompiles."""
+    """Compile every .hip source for gfx950 and link libdare.so and libdare_bench.so.  Always
+    recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(sources()))) as ex:
         results = list(ex.map(_compile, sources()))
-    objs = []
+    objs, bench_objs = [], []
     for src, obj, r in results:
         noise = "packed-fp32-ops"
         err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -46,11 +50,12 @@ def build_library(verbose=True):
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, r.stderr))
         if verbose and err.strip():
             print(err, file=sys.stderr)
-        objs.append(obj)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
+        (bench_objs if src.startswith("bench") else objs).append(obj)
+    for path, group in ((LIB_PATH, objs), (BENCH_LIB_PATH, bench_objs)):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", path] + group
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
     return LIB_PATH
 
 

@@ -24,8 +24,6 @@
 // which turns the available waves towards the key axis and fills the chip; many
 // rows use wide blocks (128 rows with two key-waves, or 256 rows with none when there are
 // enough of them), which re-read K and V less often.
-#include <cstdlib>
-
 #include "dare_common.h"
 
 namespace dare {
@@ -344,18 +342,7 @@ hipError_t launch_variant(AttnDev p, const AttnArgs& a, hipStream_t s) {
 }
 
 template <int DH>
-hipError_t launch_dh(const AttnDev& p, const AttnArgs& a, int cfg, hipStream_t s) {
-  switch (cfg) {
-    case 1: return launch_variant<DH, 4, 1, 64, 2>(p, a, s);
-    case 2: return launch_variant<DH, 4, 1, 64, 3>(p, a, s);
-    case 3: return launch_variant<DH, 2, 2, 64, 2>(p, a, s);
-    case 4: return launch_variant<DH, 1, 4, 32, 2>(p, a, s);
-    case 5: return launch_variant<DH, 4, 2, 64, 2>(p, a, s);
-    case 6: return launch_variant<DH, 2, 4, 32, 2>(p, a, s);
-    case 7: return launch_variant<DH, 4, 2, 32, 4>(p, a, s);
-    case 8: return launch_variant<DH, 8, 1, 64, 2>(p, a, s);
-    default: break;
-  }
+hipError_t launch_dh(const AttnDev& p, const AttnArgs& a, hipStream_t s) {
   // measured on MI355X: 8 waves per block.  Full rows take the wide block (128 rows, 2
   // key-waves).  Refreshed rows are few per sequence: with few (sequence, head) pairs
   // the narrow block (64 rows, 4 key-waves) is what fills the chip; with many pairs
@@ -372,8 +359,6 @@ hipError_t launch_dh(const AttnDev& p, const AttnArgs& a, int cfg, hipStream_t s
 
 }  // namespace
 
-uint64_t attn_bf16_work_bytes(int, int, int, int) { return 0; }
-
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   AttnDev p;
   p.q = static_cast<const bf16_t*>(a.q);
@@ -385,10 +370,8 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   p.seq = a.seq;
   p.d = a.n_heads * a.head_dim;
   p.scale_log2 = kLog2e / sqrtf((float)a.head_dim);
-  const char* e = getenv("DARE_ATTN_CFG");  // tuning aid: force one block shape
-  const int cfg = e ? atoi(e) : 0;
-  if (a.head_dim == 128) return launch_dh<128>(p, a, cfg, s);
-  if (a.head_dim == 64) return launch_dh<64>(p, a, cfg, s);
+  if (a.head_dim == 128) return launch_dh<128>(p, a, s);
+  if (a.head_dim == 64) return launch_dh<64>(p, a, s);
   return hipErrorInvalidValue;
 }
 

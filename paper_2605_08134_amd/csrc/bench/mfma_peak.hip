@@ -1,10 +1,16 @@
 // Register-resident MFMA loop: what the matrix pipe of this chip sustains when
 // nothing else (no LDS, no memory) is in the way.  It calibrates the datasheet peak
-// that the projection and attention kernels are measured against.
-#include "dare_common.h"
+// that the projection and attention kernels are measured against.  Benchmark aid: built
+// into libdare_bench.so, not into the product library.
+#include <hip/hip_runtime.h>
 
-namespace dare {
+#include "dare_bench.h"
+
 namespace {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kChains = 8;  // independent accumulator chains per wave
 
@@ -41,11 +47,12 @@ __global__ void __launch_bounds__(256) mfma_loop_kernel(int n_iter, int pattern,
 
 }  // namespace
 
-hipError_t launch_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops, hipStream_t s) {
+extern "C" int dare_bench_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops,
+                                    void* hip_stream) {
+  if (n_blocks < 0 || n_iter < 0 || (pattern != 0 && pattern != 1)) return 1;
   if (flops) *flops = (double)n_blocks * 4.0 * (double)n_iter * kChains * (2.0 * 32 * 32 * 16);
-  if (n_blocks == 0 || n_iter == 0) return hipSuccess;
-  hipLaunchKernelGGL(mfma_loop_kernel, dim3(n_blocks), dim3(256), 0, s, n_iter, pattern, out);
-  return hipGetLastError();
+  if (n_blocks == 0 || n_iter == 0) return 0;
+  hipLaunchKernelGGL(mfma_loop_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), n_iter,
+                     pattern, out);
+  return hipGetLastError() == hipSuccess ? 0 : 4;
 }
-
-}  // namespace dare

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "dare_common.h"
 
@@ -24,8 +25,6 @@ struct dare_ctx {
   size_t q_new_elems;
   int32_t* sel_idx;    // [max tokens]
   int32_t* sel_off;    // [max_batch + 1]
-  void* attn_work;
-  uint64_t attn_work_bytes;
   // the block around the layer (dare_block_attach)
   bool has_block, has_bias;
   dare_block_config block;
@@ -38,12 +37,11 @@ struct dare_ctx {
   bool stats_on;
   float* tau_dev;      // [max_batch] thresholds of the last quantile step
   float* scores_buf;   // [max tokens] scores when the caller passes none
-  double* stat_sum;    // one fp64 sum followed by one 64-bit count
+  double* stat_sum;    // [max_batch] fp64 sums followed by [max_batch] 64-bit counts, one slot per sequence
   // frozen prefix
   int prefix;          // tokens [0, prefix) of every sequence are frozen
   int32_t* act_idx;    // [max tokens] ids of the tokens that are not frozen
   int32_t* act_off;    // [max_batch + 1] offsets of the sequences in act_idx
-  int act_batch, act_seq, act_prefix;  // what act_idx / act_off currently describe
   std::string err;
 };
 
@@ -87,8 +85,7 @@ struct DeviceGuard {
 
 void free_ctx(dare_ctx* c) {
   if (!c) return;
-  void* bufs[] = {c->wqkv_t, c->wo_t, c->q_buf, c->attn_buf, c->q_new, c->sel_idx, c->sel_off,
-                  c->attn_work, c->gain, c->bias, c->h_buf, c->rope_table, c->tau_dev, c->scores_buf,
+  void* bufs[] = {c->wqkv_t, c->wo_t, c->q_buf, c->attn_buf, c->q_new, c->sel_idx, c->sel_off, c->gain, c->bias, c->h_buf, c->rope_table, c->tau_dev, c->scores_buf,
                   c->stat_sum, c->act_idx, c->act_off};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
@@ -144,7 +141,7 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, 
   c->cfg = *cfg;
   c->esize = cfg->dtype == DARE_BF16 ? 2 : 4;
   c->score_width = cfg->score_head < 0 ? cfg->hidden : cfg->head_dim;
-  c->wqkv_t = c->wo_t = c->q_buf = c->attn_buf = c->attn_work = nullptr;
+  c->wqkv_t = c->wo_t = c->q_buf = c->attn_buf = nullptr;
   c->q_new = nullptr;
   c->sel_idx = c->sel_off = nullptr;
   c->has_block = c->has_bias = false;
@@ -156,11 +153,7 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, 
   c->stat_sum = nullptr;
   c->prefix = 0;
   c->act_idx = c->act_off = nullptr;
-  c->act_batch = c->act_seq = c->act_prefix = -1;
   const size_t d = cfg->hidden;
-  c->attn_work_bytes = cfg->dtype == DARE_BF16
-                           ? attn_bf16_work_bytes(cfg->max_batch, cfg->max_seq, cfg->n_heads, cfg->head_dim)
-                           : 0;
   // room for 8 k-range slabs of the scored columns up to 4096 tokens (beyond that the
   // projection has enough tiles without cutting k)
   c->q_new_elems = (size_t)max_tok * c->score_width;
@@ -173,7 +166,6 @@ dare_status dare_create(const dare_config* cfg, const void* wq, const void* wk, 
       {(void**)&c->q_new, c->q_new_elems * sizeof(float)},
       {(void**)&c->sel_idx, (size_t)max_tok * sizeof(int32_t)},
       {(void**)&c->sel_off, ((size_t)cfg->max_batch + 1) * sizeof(int32_t)},
-      {&c->attn_work, (size_t)c->attn_work_bytes},
   };
   for (auto& a : allocs) {
     if (a.bytes == 0) continue;
@@ -251,13 +243,10 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
   const int P = ctx->prefix;
   const bool pre = P > 0;
   const int n_act = batch * (seq - P);
-  if (pre && (ctx->act_batch != batch || ctx->act_seq != seq || ctx->act_prefix != P)) {
-    if ((e = launch_active_list(batch, seq, P, ctx->act_idx, ctx->act_off, s)) != hipSuccess)
-      return fail_hip(ctx, e, "active-row list");
-    ctx->act_batch = batch;
-    ctx->act_seq = seq;
-    ctx->act_prefix = P;
-  }
+  // (written by every step that has a prefix: a list cached across calls would be wrong as
+  // soon as a step is recorded into a graph and replayed between eager steps of another shape)
+  if (pre && (e = launch_active_list(batch, seq, P, ctx->act_idx, ctx->act_off, s)) != hipSuccess)
+    return fail_hip(ctx, e, "active-row list");
   const int32_t* act_idx = pre ? ctx->act_idx : nullptr;
 
   // 1. Query projection feeding the score (Alg. 1/2 line 2), together with whatever
@@ -314,7 +303,7 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
     const int rank = by_rate ? (int)ceilf(threshold * (float)(seq - P)) : -1;
     double* sum = ctx->stats_on ? ctx->stat_sum : nullptr;
     e = launch_quantile_mask(sc, batch, seq, P, seq - P, rank, mode == DARE_MODE_DENSE, ctx->tau_dev, reuse_mask,
-                             sum, reinterpret_cast<unsigned long long*>(sum ? sum + 1 : nullptr), s);
+                             sum, reinterpret_cast<unsigned long long*>(sum ? sum + cf.max_batch : nullptr), s);
     if (e != hipSuccess) return fail_hip(ctx, e, "threshold selection");
   }
 
@@ -383,8 +372,6 @@ dare_status step_impl(dare_ctx* ctx, int mode, float threshold, int batch, int s
   a.idx = sel_o ? ctx->sel_idx : act_idx;
   a.sel_off = sel_o ? ctx->sel_off : (pre ? ctx->act_off : nullptr);
   a.many_rows = !sel_o && pre;
-  a.work = ctx->attn_work;
-  a.work_bytes = ctx->attn_work_bytes;
   if ((e = attn(ctx, a, s)) != hipSuccess) return fail_hip(ctx, e, "attention");
 
   // 6. Output projection (Alg. 1 line 11; Alg. 2 lines 9-11 with the cache after Wo).
@@ -604,7 +591,7 @@ dare_status ensure_threshold_buffers(dare_ctx* ctx) {
   struct { void** p; size_t bytes; } need[] = {
       {(void**)&ctx->tau_dev, (size_t)ctx->cfg.max_batch * sizeof(float)},
       {(void**)&ctx->scores_buf, max_tok * sizeof(float)},
-      {(void**)&ctx->stat_sum, 2 * sizeof(double)},
+      {(void**)&ctx->stat_sum, 2 * (size_t)ctx->cfg.max_batch * sizeof(double)},
   };
   for (auto& n : need) {
     if (*n.p) continue;
@@ -674,7 +661,7 @@ dare_status dare_drift_stats_enable(dare_ctx* ctx, int on, void* hip_stream) {
     dare_status st = ensure_threshold_buffers(ctx);
     if (st != DARE_OK) return st;
     // ordered on the stream after the steps already enqueued
-    e = launch_zero_words(ctx->stat_sum, 2, static_cast<hipStream_t>(hip_stream));
+    e = launch_zero_words(ctx->stat_sum, 2 * ctx->cfg.max_batch, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(ctx, e, "statistics reset");
   }
   ctx->stats_on = on != 0;
@@ -689,14 +676,22 @@ dare_status dare_drift_stats_read(dare_ctx* ctx, double* mean, int64_t* count, v
   hipError_t e = guard.enter(ctx->cfg.device);
   if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  double host[2];
-  if ((e = hipMemcpyAsync(host, ctx->stat_sum, sizeof(host), hipMemcpyDeviceToHost, s)) != hipSuccess)
+  const int nb = ctx->cfg.max_batch;
+  std::vector<double> host(2 * (size_t)nb);
+  if ((e = hipMemcpyAsync(host.data(), ctx->stat_sum, host.size() * sizeof(double), hipMemcpyDeviceToHost, s)) !=
+      hipSuccess)
     return fail_hip(ctx, e, "hipMemcpyAsync");
   if ((e = hipStreamSynchronize(s)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
-  uint64_t n;
-  std::memcpy(&n, &host[1], sizeof(n));
+  double sum = 0.0;
+  uint64_t n = 0;
+  for (int b = 0; b < nb; ++b) {  // per-sequence slots, added in sequence order
+    uint64_t nb_b;
+    std::memcpy(&nb_b, &host[(size_t)nb + b], sizeof(nb_b));
+    sum += host[b];
+    n += nb_b;
+  }
   *count = (int64_t)n;
-  *mean = n ? host[0] / (double)n : 0.0;
+  *mean = n ? sum / (double)n : 0.0;
   return DARE_OK;
 }
 
@@ -826,7 +821,7 @@ dare_status dare_k_compact(const uint8_t* mask, int batch, int seq, int32_t* sel
 
 dare_status dare_k_attention(int dtype, const void* q, const void* k, const void* v, void* out, int batch,
                              int seq, int n_heads, int head_dim, const int32_t* idx,
-                             const int32_t* sel_off, void* work, uint64_t work_bytes, void* hip_stream) {
+                             const int32_t* sel_off, void* hip_stream) {
   if (!q || !k || !v || !out || batch < 1 || seq < 1 || n_heads < 1) return DARE_ERR_INVALID_ARG;
   if (dtype != DARE_F32 && dtype != DARE_BF16) return DARE_ERR_INVALID_ARG;
   if ((idx == nullptr) != (sel_off == nullptr)) return DARE_ERR_INVALID_ARG;
@@ -843,8 +838,6 @@ dare_status dare_k_attention(int dtype, const void* q, const void* k, const void
   a.head_dim = head_dim;
   a.idx = idx;
   a.sel_off = sel_off;
-  a.work = work;
-  a.work_bytes = work_bytes;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e = dtype == DARE_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
@@ -854,13 +847,6 @@ dare_status dare_k_copy_rows(const void* src, void* dst, int n_rows, int row_byt
                              const int32_t* m_dev, void* hip_stream) {
   if (!src || !dst || n_rows < 0 || row_bytes < 16 || row_bytes % 16 != 0) return DARE_ERR_INVALID_ARG;
   hipError_t e = launch_copy_rows(src, dst, n_rows, row_bytes, idx, m_dev, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
-}
-
-dare_status dare_k_calib_mfma(int n_blocks, int n_iter, int pattern, float* out, double* flops,
-                              void* hip_stream) {
-  if (n_blocks < 0 || n_iter < 0 || (pattern != 0 && pattern != 1)) return DARE_ERR_INVALID_ARG;
-  hipError_t e = launch_mfma_loop(n_blocks, n_iter, pattern, out, flops, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? DARE_OK : DARE_ERR_HIP;
 }
 

@@ -85,12 +85,9 @@ struct AttnArgs {
   const int32_t* idx;      // optional selected rows
   const int32_t* sel_off;  // [batch+1] when idx != nullptr
   bool many_rows;          // the listed rows are most of each sequence (a frozen prefix), not a few
-  void* work;
-  uint64_t work_bytes;
 };
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t s);
-uint64_t attn_bf16_work_bytes(int batch, int seq, int n_heads, int head_dim);
 
 hipError_t launch_pack_weight(int dtype, const void* w, int rows_k, int cols_n, void* wt,
                               int ldwt, hipStream_t s);
@@ -105,7 +102,6 @@ hipError_t launch_quantile_mask(const float* scores, int batch, int stride, int 
                                 unsigned long long* stat_count, hipStream_t s);
 hipError_t launch_zero_words(void* p, int n, hipStream_t s);
 hipError_t launch_active_list(int batch, int seq, int prefix, int32_t* act_idx, int32_t* act_off, hipStream_t s);
-hipError_t launch_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops, hipStream_t s);
 hipError_t launch_copy_rows(const void* src, void* dst, int n_rows, int row_bytes,
                             const int32_t* idx, const int32_t* m_dev, hipStream_t s);
 // rows r = 0 .. n_rows-1; with seq > 0 row r is token (r / (seq - prefix)) * seq + prefix + r % (seq - prefix)

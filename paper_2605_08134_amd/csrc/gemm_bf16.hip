@@ -38,7 +38,6 @@
 // reads, so a step with 50 refreshed rows does not pay for a 256-row tile and no
 // host round trip is needed.  The grid is sized for the worst case; workgroups
 // beyond the tiles that exist return at once.
-#include <cstdlib>
 #include <type_traits>
 
 #include "dare_common.h"
@@ -639,20 +638,20 @@ __device__ __forceinline__ int derive_rows(const GemmDev& p, int32_t* list, int*
       p.sel_idx_out[r] = list[r];
       if (p.sel_idx_out2) p.sel_idx_out2[r] = list[r];
     }
-    if (tid <= p.sel_batch) {
-      // refreshed tokens in front of sequence tid: first list position holding a token >= tid * seq
-      auto before = [&](int b) {
-        const int key = b * p.sel_seq;
-        int lo = 0, hi = total;
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (list[mid] < key) lo = mid + 1; else hi = mid;
-        }
-        return lo;
-      };
-      const int off = before(tid);
-      p.sel_off_out[tid] = off;
-      if (p.sel_count_out && tid < p.sel_batch) p.sel_count_out[tid] = before(tid + 1) - off;
+    // refreshed tokens in front of sequence b: first list position holding a token >= b * seq
+    auto before = [&](int b) {
+      const int key = b * p.sel_seq;
+      int lo = 0, hi = total;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (list[mid] < key) lo = mid + 1; else hi = mid;
+      }
+      return lo;
+    };
+    for (int b = tid; b <= p.sel_batch; b += 512) {  // (a batch may have more sequences than threads)
+      const int off = before(b);
+      p.sel_off_out[b] = off;
+      if (p.sel_count_out && b < p.sel_batch) p.sel_count_out[b] = before(b + 1) - off;
     }
   }
   return total;
@@ -786,25 +785,7 @@ hipError_t launch_rows_wide(const GemmArgs& g, hipStream_t s) {
 
 }  // namespace
 
-// cfg: 0 = choose by shape; other values force one configuration (tuning aid).
-hipError_t launch_gemm_bf16_cfg(const GemmArgs& g, int cfg, hipStream_t s) {
-  switch (cfg) {
-    case 1: return launch_fixed<128, 128, 2, 2, 4>(g, s);
-    case 2: return launch_fixed<128, 128, 2, 2, 3>(g, s);
-    case 3: return launch_fixed<128, 128, 2, 2, 2>(g, s);
-    case 4: return launch_fixed<256, 256, 2, 4, 2>(g, s);
-    case 5: return launch_fixed<256, 128, 4, 2, 3>(g, s);
-    case 7: return launch_fixed<128, 64, 4, 1, 4>(g, s);
-    case 8: return launch_fixed<256, 128, 2, 2, 3>(g, s);
-    case 9: return launch_fixed<256, 192, 4, 2, 2>(g, s);
-    case 10: return launch_fixed<256, 192, 2, 2, 2>(g, s);
-    case 11: return launch_fixed<256, 64, 4, 1, 3>(g, s);
-    case 12: return launch_fixed<64, 64, 2, 2, 4>(g, s);
-    case 13: return launch_fixed<128, 128, 4, 2, 4>(g, s);
-    case 14: return launch_fixed<128, 256, 2, 4, 2>(g, s);
-    case 21: return launch_rows_wide(g, s);
-    default: break;
-  }
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (g.m_dev || g.sel_mask) return launch_rows_wide(g, s);
   // Row count known on the host.  Measured on MI355X (256 CUs): 256 x 256 tiles have
   // the least LDS-fill traffic per flop and win once they fill the chip; 256 x 192
@@ -816,11 +797,6 @@ hipError_t launch_gemm_bf16_cfg(const GemmArgs& g, int cfg, hipStream_t s) {
   if (g.n % 256 == 0 && tiles(256, 256) >= 224) return launch_fixed<256, 256, 2, 4, 2>(g, s);
   if (g.m_max > 64 && g.n % 128 == 0 && tiles(128, 128) >= 64) return launch_fixed<128, 128, 4, 2, 4>(g, s);
   return launch_fixed<64, 64, 2, 2, 4>(g, s);
-}
-
-hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
-  const char* e = getenv("DARE_GEMM_CFG");  // tuning aid: force one tile configuration
-  return launch_gemm_bf16_cfg(g, e ? atoi(e) : 0, s);
 }
 
 }  // namespace dare

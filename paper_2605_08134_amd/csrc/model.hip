@@ -110,7 +110,6 @@ struct dare_model {
   uint8_t* mask;      // [max tokens] reuse mask of the layer being run
   int32_t* act_idx;   // frozen prefix: rows that are not frozen
   int32_t* act_off;
-  int act_batch, act_seq, act_prefix;
   int rule, prefix;
   std::vector<void*> owned;
   std::string err;
@@ -201,7 +200,6 @@ dare_status dare_model_create(const dare_model_config* cfg, void* hip_stream, da
   m->layers.assign(cfg->n_layers, nullptr);
   m->mem.assign(cfg->n_layers, dare_model::LayerMem{});
   m->embed = m->final_gain = m->head_t = nullptr;
-  m->act_batch = m->act_seq = m->act_prefix = -1;
   m->rule = DARE_RULE_SCORE;
   m->prefix = 0;
   const size_t d = cfg->hidden, es = m->esize, tok = (size_t)max_tok;
@@ -384,13 +382,8 @@ dare_status dare_model_step(dare_model* m, const int32_t* modes, const float* th
   const bool pre = P > 0;
   const int n_act = batch * (seq - P);
   hipError_t e;
-  if (pre && (m->act_batch != batch || m->act_seq != seq || m->act_prefix != P)) {
-    if ((e = launch_active_list(batch, seq, P, m->act_idx, m->act_off, s)) != hipSuccess)
-      return mfail_hip(m, e, "active-row list");
-    m->act_batch = batch;
-    m->act_seq = seq;
-    m->act_prefix = P;
-  }
+  if (pre && (e = launch_active_list(batch, seq, P, m->act_idx, m->act_off, s)) != hipSuccess)
+    return mfail_hip(m, e, "active-row list");
   const int32_t* act = pre ? m->act_idx : nullptr;
   char* tr = static_cast<char*>(trace);
   auto snapshot = [&](int slot) -> hipError_t {

@@ -191,8 +191,9 @@ __global__ void __launch_bounds__(256) compact_kernel(const uint8_t* __restrict_
 // the k-th smallest of its drift scores, found exactly by a radix select over an
 // order-preserving 32-bit key (four passes of 8 bits, most significant first; NaN keys
 // sort last).  One workgroup per sequence; it then writes the reuse decision s <= tau of
-// its tokens and adds the sequence's score sum and count to the running drift statistics
-// (the layer-wise mean drift of the same section).
+// its tokens and adds the sequence's score sum and count to slot b of the running drift
+// statistics (the layer-wise mean drift of the same section; one slot per sequence, no
+// atomics).
 //   rank > 0: select and decide; rank = 0: tau = -inf, nothing reused; rank < 0: statistics
 //   only (mask and tau untouched).
 // ---------------------------------------------------------------------------
@@ -296,8 +297,10 @@ __global__ void __launch_bounds__(kSelectThreads) quantile_mask_kernel(
         t += red_sum[w];
         n += red_cnt[w];
       }
-      atomicAdd(stat_sum, t);
-      atomicAdd(stat_count, n);
+      // slot b belongs to this workgroup alone and steps are ordered by the stream: a plain
+      // read-modify-write, the same sum from run to run (the reader adds the slots in order)
+      stat_sum[b] += t;
+      stat_count[b] += n;
     }
   }
 }

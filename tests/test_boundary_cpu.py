@@ -35,6 +35,16 @@ def test_every_declared_symbol_is_exported(L):
         assert getattr(L, name) is not None
 
 
+def test_bench_library_exports_what_its_header_declares(L):
+    text = open(os.path.join(ROOT, "include", "dare_bench.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(dare_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(B.BENCH_EXPORTS)
+    for name in declared:
+        assert getattr(B.bench_lib(), name) is not None
+        assert not hasattr(L, name)          # benchmark aids stay out of the product library
+
+
 def test_version(L):
     assert re.fullmatch(r"\d+\.\d+", B.dare_version())
 
