@@ -17,6 +17,12 @@ Comparison rules (stated once here, used by every parity test):
     therefore applied to the error IN EXCESS of the final storage rounding,
         excess = max(0, |gpu - exact| - half_ulp_bf16(exact)),   max excess / rms <= 2e-2,
     and the plain max |gpu - exact| / rms is reported next to it.
+  * bf16 storage, second gate, independent of where the kernels round: every GPU tensor is
+    also compared with the PLAIN float64 oracle (no storage rounding anywhere: the
+    definition).  Two figures are bounded: the rms error rms(gpu - definition) /
+    rms(definition), which the few many-sigma elements do not dominate, and the plain
+    max |gpu - definition| / rms(definition).  The bounds (DEF_RMS_TOL, DEF_MAX_TOL) sit just
+    above what five bf16 roundings (Q, K, V, attention rows, output) give on these inputs.
   * rows the step must not touch (reused K/V/O rows) equal the input bit for bit.
 """
 import numpy as np
@@ -27,6 +33,14 @@ from paper_2605_08134_amd import synth
 
 TOL = {"bf16": 2e-2, "f32": 1e-4}
 TIE_BAND = 1e-6
+# bf16 path against the unrounded float64 definition (see the header); measured on the
+# LLaDA-8B-shaped layer: rms 0.35-0.5 %, max 3.7-3.9 % of the output's rms
+DEF_RMS_TOL = 1e-2
+DEF_MAX_TOL = 4.5e-2
+
+
+def orc_mode_name(mode):
+    return {orc.MODE_DENSE: "dense", orc.MODE_KV: "kv", orc.MODE_O: "o", orc.MODE_KVO: "kvo"}[mode]
 
 
 def tdtype(dtype):
@@ -57,6 +71,40 @@ def rel_err(got, want):
     if want.size == 0:
         return 0.0
     return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - want))) / max(rms, 1e-30)
+
+
+def rms_err(got, want):
+    """rms(got - want) / rms(want)."""
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    diff = np.asarray(got, dtype=np.float64) - want
+    return float(np.sqrt(np.mean(diff ** 2))) / max(rms, 1e-30)
+
+
+def check_against_definition(got, plain, mode):
+    """The bf16 path against the oracle's plain float64 step (storage=None) on the same
+    inputs: rms and max error of out, k_cache and v_cache relative to the rms of the
+    definition's tensor, over the rows this step computed (a reused row is a copy of a
+    cache row and is compared bit for bit elsewhere).  Returns the measured figures."""
+    info = {}
+    fresh = np.asarray(plain["reuse_mask"]) == 0
+    assert np.array_equal(np.asarray(got["reuse_mask"]) == 0, fresh)
+    every = np.ones_like(fresh)
+    rows_of = {"out": fresh if mode in (orc.MODE_O, orc.MODE_KVO) else every,
+               "k_cache": fresh if mode in (orc.MODE_KV, orc.MODE_KVO) else every,
+               "v_cache": fresh if mode in (orc.MODE_KV, orc.MODE_KVO) else every}
+    for key, rows in rows_of.items():
+        g = np.asarray(got[key], dtype=np.float64)[rows]
+        w = np.asarray(plain[key], dtype=np.float64)[rows]
+        if w.size == 0:
+            continue
+        info[key + "_rms"] = rms_err(g, w)
+        info[key + "_max"] = rel_err(g, w)
+        assert info[key + "_rms"] <= DEF_RMS_TOL, "%s: rms error %g of rms" % (key, info[key + "_rms"])
+        assert info[key + "_max"] <= DEF_MAX_TOL, "%s: max error %g of rms" % (key, info[key + "_max"])
+    return info
 
 
 def half_ulp_bf16(x):
@@ -164,11 +212,13 @@ class GpuLayer:
         return res
 
 
-def check_step(got, want, state_in, mode, tau, dtype, expect_no_ties=True):
-    """Compare one GPU step with the oracle's.  Returns a dict of measured errors."""
+def check_step(got, want, state_in, mode, tau, dtype, expect_no_ties=True, tie_band=TIE_BAND):
+    """Compare one GPU step with the oracle's.  Returns a dict of measured errors.
+    tie_band: how far a GPU score may lie from the oracle's, and the width of the band around
+    the threshold inside which a decision may fall either way."""
     tol = TOL[dtype]
     s_or = want["scores"]
-    ties = np.abs(s_or - float(np.float32(tau))) < TIE_BAND if mode != orc.MODE_DENSE else np.zeros_like(s_or, bool)
+    ties = np.abs(s_or - float(np.float32(tau))) < tie_band if mode != orc.MODE_DENSE else np.zeros_like(s_or, bool)
     n_ties = int(ties.sum())
     assert n_ties <= max(0.01 * ties.size, 0 if expect_no_ties else 16), "too many ties: %d" % n_ties
     if expect_no_ties:
@@ -176,7 +226,7 @@ def check_step(got, want, state_in, mode, tau, dtype, expect_no_ties=True):
     info = {"ties": n_ties}
 
     info["score_err"] = float(np.max(np.abs(got["scores"].astype(np.float64) - s_or)))
-    assert info["score_err"] < TIE_BAND
+    assert info["score_err"] < tie_band
 
     # masks and lists, bit-exact outside the ties
     gm, wm = got["reuse_mask"], want["reuse_mask"]

@@ -108,6 +108,54 @@ def test_gemm_selected_rows_wide_output(B, n_tok, count):
         assert_close(got[rows], want, "bf16")
 
 
+_LONG_K = {}
+
+
+def _long_k_operands(n):
+    """a [1200, 4096] and w [4096, n], drawn once per width (the wide one is 200 MB)."""
+    if n not in _LONG_K:
+        r = _rng(4096 + n)
+        a = store(r.standard_normal((1200, 4096), dtype=np.float32), "bf16")
+        w = store(r.standard_normal((4096, n), dtype=np.float32) * np.float32(0.02), "bf16")
+        _LONG_K.clear()
+        _LONG_K[n] = (a, w)
+    return _LONG_K[n]
+
+
+@pytest.mark.parametrize("n,count,shape", [
+    (1024, 1100, "64 x 64, two tiles per workgroup"),
+    (4096, 24, "register-fed stream, two row blocks"),
+    (4096, 400, "128 x 64"),
+    (12288, 24, "64 x 64, one tile per workgroup"),
+    (12288, 100, "128 x 48"),
+    (12288, 205, "128 x 96"),
+    (12288, 400, "128 x 192"),
+    (12288, 600, "128 x 128"),
+    (12288, 900, "256 x 192"),
+])
+def test_gemm_selected_rows_long_k(B, n, count, shape):
+    """The device-side tile choice at k = 4096 (64 k-steps: the operand ring of every shape
+    runs in its steady state, not only its prologue), rows gathered through a list, output
+    rows written at their token index."""
+    a, w = _long_k_operands(n)
+    n_tok, k = a.shape
+    r = _rng(count)
+    seg = n if n <= 4096 else 4096
+    rows = np.sort(r.permutation(n_tok)[:count]).astype(np.int32)
+    idx = np.full(n_tok, 10 ** 6, dtype=np.int32)
+    idx[:count] = rows
+    wt = B.dare_k_pack_weight(dev(w, "bf16"))
+    outs = [torch.full((n_tok, seg), 3.0, dtype=torch.bfloat16, device="cuda") for _ in range(n // seg)]
+    m_dev = torch.tensor([count], dtype=torch.int32, device="cuda")
+    B.dare_k_gemm(dev(a, "bf16"), wt, outs, seg, idx=dev(idx), m_dev=m_dev, m_max=n_tok)
+    torch.cuda.synchronize()
+    got = np.concatenate([host(o) for o in outs], axis=1)
+    untouched = np.setdiff1d(np.arange(n_tok), rows)
+    assert np.all(got[untouched] == 3.0)
+    want = a[rows].astype(np.float64) @ w.astype(np.float64)
+    assert_close(got[rows], want, "bf16")
+
+
 def test_gemm_k_parts_feed_the_score(B):
     # the scored-columns projection cut along k: slabs of partial sums that the score
     # kernel adds up, against the uncut projection and the oracle's score
