@@ -33,10 +33,12 @@ from paper_2605_08134_amd import synth
 
 TOL = {"bf16": 2e-2, "f32": 1e-4}
 TIE_BAND = 1e-6
-# bf16 path against the unrounded float64 definition (see the header); measured on the
-# LLaDA-8B-shaped layer: rms 0.35-0.5 %, max 3.7-3.9 % of the output's rms
-DEF_RMS_TOL = 1e-2
-DEF_MAX_TOL = 4.5e-2
+# bf16 path against the unrounded float64 definition (see the header).  Measured on the
+# LLaDA-8B-shaped layer, all modes, 1 to 1024 refreshed rows of 1024 tokens and 8 x 2048 tokens:
+# rms error 0.37-0.53 % of the output's rms (K, V: 0.17 %); max error 1.5-4.1 % (1024 tokens),
+# up to 4.6 % (8 x 2048: the maximum is taken over 8 times as many elements; K, V: 1.2 %).
+DEF_RMS_TOL = 7e-3
+DEF_MAX_TOL = 5.5e-2
 
 
 def orc_mode_name(mode):
@@ -212,10 +214,11 @@ class GpuLayer:
         return res
 
 
-def check_step(got, want, state_in, mode, tau, dtype, expect_no_ties=True, tie_band=TIE_BAND):
+def check_step(got, want, state_in, mode, tau, dtype, expect_no_ties=True, tie_band=TIE_BAND, q_prev_tol=1e-4):
     """Compare one GPU step with the oracle's.  Returns a dict of measured errors.
     tie_band: how far a GPU score may lie from the oracle's, and the width of the band around
-    the threshold inside which a decision may fall either way."""
+    the threshold inside which a decision may fall either way.  q_prev_tol: bound on the
+    fp32 score cache (max error / rms)."""
     tol = TOL[dtype]
     s_or = want["scores"]
     ties = np.abs(s_or - float(np.float32(tau))) < tie_band if mode != orc.MODE_DENSE else np.zeros_like(s_or, bool)
@@ -248,7 +251,7 @@ def check_step(got, want, state_in, mode, tau, dtype, expect_no_ties=True, tie_b
     for key, ref in (("out", exact["out"]), ("o_cache", exact["out"]), ("k_cache", exact["k_cache"]),
                      ("v_cache", exact["v_cache"]), ("q_prev", want["q_prev"])):
         if key == "q_prev" or dtype == "f32":
-            t = 1e-4
+            t = q_prev_tol if key == "q_prev" else 1e-4
             info[key] = rel_err(got[key], ref)
         else:
             t = tol

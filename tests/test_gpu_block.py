@@ -289,7 +289,10 @@ def test_block_bf16_from_x_end_to_end(norm, mode):
     for tau in (-1.0, pu.gap_threshold(s, 0.6, min_gap=4 * H_FLIP_BAND), 2.5):
         want = run(mode, tau, case["x_cur"], state)
         got = gb.block_step(mode, tau, case["x_cur"], state)
-        info = pu.check_step(dict(got, out=got["o_cache"]), want, state, mode, tau, "bf16", tie_band=H_FLIP_BAND)
+        # (a flipped element of h, one bf16 ulp of a value of up to 4, times one weight of up to
+        # 0.09 shows up in the fp32 score cache itself: 3e-3 of a query rms of 0.45)
+        info = pu.check_step(dict(got, out=got["o_cache"]), want, state, mode, tau, "bf16", tie_band=H_FLIP_BAND,
+                             q_prev_tol=1e-2)
         assert info["ties"] == 0
         exact = want["exact"]["block_out"]
         rms_o = float(np.sqrt(np.mean(np.asarray(want["exact"]["out"], dtype=np.float64) ** 2)))

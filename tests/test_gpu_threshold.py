@@ -35,11 +35,11 @@ def _select(B, s, phi, force=False, stats=False):
     sd = dev(s)
     mask = torch.full(s.shape, 7, dtype=torch.uint8, device="cuda")
     tau = torch.full((s.shape[0],), 123.0, dtype=torch.float32, device="cuda")
-    ssum = torch.zeros(1, dtype=torch.float64, device="cuda") if stats else None
-    scnt = torch.zeros(1, dtype=torch.int64, device="cuda") if stats else None
+    ssum = torch.zeros(s.shape[0], dtype=torch.float64, device="cuda") if stats else None   # one slot per sequence
+    scnt = torch.zeros(s.shape[0], dtype=torch.int64, device="cuda") if stats else None
     B.dare_k_quantile_mask(sd, phi, mask, tau, force, ssum, scnt)
     torch.cuda.synchronize()
-    return host(tau), host(mask), (None if not stats else (float(ssum.item()), int(scnt.item())))
+    return host(tau), host(mask), (None if not stats else (host(ssum), host(scnt)))
 
 
 @pytest.mark.parametrize("batch,seq", [(1, 1), (3, 7), (2, 1024), (5, 1000), (2, 5000), (8, 2048)])
@@ -77,17 +77,22 @@ def test_radix_select_force_refresh_and_statistics(B):
     assert not mask.any()
     assert np.array_equal(tau, orc.quantile_threshold(s, 0.5))
     ok = ~np.isnan(s)
-    assert st[1] == int(ok.sum())
-    assert abs(st[0] - float(s[ok].astype(np.float64).sum())) <= 1e-9 * st[1]
-    # statistics only: mask and tau untouched
+    assert np.array_equal(st[1], ok.sum(axis=1))                   # per-sequence slots
+    want_sum = np.where(ok, s, 0.0).astype(np.float64).sum(axis=1)
+    assert np.all(np.abs(st[0] - want_sum) <= 1e-9 * st[1])
+    # statistics only: mask and tau untouched; a second call adds to the same slots, and the
+    # sums are the same bits from run to run (no atomics)
     sd = dev(s)
     mask2 = torch.full(s.shape, 7, dtype=torch.uint8, device="cuda")
-    ssum = torch.zeros(1, dtype=torch.float64, device="cuda")
-    scnt = torch.zeros(1, dtype=torch.int64, device="cuda")
-    B.dare_k_quantile_mask(sd, -1.0, mask2, None, False, ssum, scnt)
+    ssum = torch.zeros(4, dtype=torch.float64, device="cuda")
+    scnt = torch.zeros(4, dtype=torch.int64, device="cuda")
     B.dare_k_quantile_mask(sd, -1.0, mask2, None, False, ssum, scnt)
     torch.cuda.synchronize()
-    assert (host(mask2) == 7).all() and int(scnt.item()) == 2 * int(ok.sum())
+    assert np.array_equal(host(ssum), st[0])
+    B.dare_k_quantile_mask(sd, -1.0, mask2, None, False, ssum, scnt)
+    torch.cuda.synchronize()
+    assert (host(mask2) == 7).all() and np.array_equal(host(scnt), 2 * ok.sum(axis=1))
+    assert np.array_equal(host(ssum), 2 * st[0])
 
 
 # ------------------------------------------------------------------ the step under the quantile rule
