@@ -232,6 +232,48 @@ int dare_policy_mode(int mode, int layer, int step, int skip_layers, int refresh
  */
 dare_status dare_set_prefix(dare_ctx* ctx, int prefix_len);
 
+/*
+ * dare_layer_step for callers that cannot allocate device memory: code under HIP graph
+ * capture that must not meet an allocation, tight serving loops, harnesses that forbid
+ * hipMalloc.  It needs no context and calls no hipMalloc, hipFree or any other allocating
+ * routine, at the first call or later: the scratch that dare_create would allocate (queries,
+ * attention rows, the fp32 scored query, the refreshed-row list) lives in a static device
+ * array inside the library, which every GPU the library runs on holds until the process
+ * ends.
+ *
+ *   cfg      as for dare_create; max_batch and max_seq are not used
+ *   wqkv_t   device, [3 * hidden, hidden]: Wq, Wk, Wv, each re-packed by
+ *            dare_k_pack_weight (ldwt = hidden) and stored one after the other
+ *   wo_t     device, [hidden, hidden]: Wo re-packed the same way
+ *   the other arguments, the modes and the results are those of dare_layer_step (score
+ *   rule; no frozen prefix, no block).
+ *
+ * Limits (DARE_ERR_UNSUPPORTED with a message naming the limit):
+ *   batch * seq * hidden * sizeof(dtype)  <= DARE_STATIC_MAX_ROW_BYTES
+ *   batch * seq * scored width            <= DARE_STATIC_MAX_SCORE_ELEMS
+ * (scored width = head_dim, or hidden with score_head = -1); 1024 tokens of hidden 4096 in
+ * bf16 fit exactly.  The array takes about 20.5 MiB per GPU.
+ *
+ * All calls on one GPU share that GPU's array: two calls whose kernels overlap (different
+ * streams, different threads) race; order them on one stream.  Nothing in the scratch has to
+ * start at zero, and nothing is kept between calls: every word a kernel reads was written
+ * earlier in the same call.
+ *
+ * dare_static_init(device) looks up the array's device address ahead of time (the step
+ * call does it by itself on first use on a device); call it before a graph capture starts.
+ * Errors: as dare_layer_step, plus the config errors of dare_create; the text is read with
+ * dare_last_error(NULL) on the calling thread.
+ */
+#define DARE_STATIC_MAX_ROW_BYTES (8u << 20)
+#define DARE_STATIC_MAX_SCORE_ELEMS (1u << 20)
+dare_status dare_static_init(int device);
+dare_status dare_layer_step_static(const dare_config* cfg, const void* wqkv_t, const void* wo_t,
+                                   int mode, float threshold, int batch, int seq,
+                                   const void* hidden, float* q_prev, void* k_cache,
+                                   void* v_cache, void* o_cache, void* out,
+                                   uint8_t* reuse_mask, int32_t* sel_idx, int32_t* sel_count,
+                                   float* scores, void* hip_stream);
+
 /* Free a context and its device memory.  NULL is a no-op. */
 dare_status dare_destroy(dare_ctx* ctx);
 

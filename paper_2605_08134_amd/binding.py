@@ -19,6 +19,7 @@ MODE_NAMES = {MODE_DENSE: "dense", MODE_KV: "kv", MODE_O: "o", MODE_KVO: "kvo"}
 
 EXPORTS = (
     "dare_create", "dare_layer_step", "dare_destroy", "dare_last_error", "dare_version",
+    "dare_static_init", "dare_layer_step_static",
     "dare_k_pack_weight", "dare_k_gemm", "dare_k_score", "dare_k_compact",
     "dare_k_attention", "dare_k_copy_rows",
     "dare_block_attach", "dare_block_step", "dare_k_gemm_rope", "dare_k_rope_table",
@@ -95,6 +96,10 @@ def lib():
     L.dare_create.restype = i32
     L.dare_layer_step.argtypes = [vp, i32, f32, i32, i32] + [vp] * 11
     L.dare_layer_step.restype = i32
+    L.dare_static_init.argtypes = [i32]
+    L.dare_static_init.restype = i32
+    L.dare_layer_step_static.argtypes = [ctypes.POINTER(DareConfig), vp, vp, i32, f32, i32, i32] + [vp] * 11
+    L.dare_layer_step_static.restype = i32
     L.dare_destroy.argtypes = [vp]
     L.dare_destroy.restype = i32
     L.dare_last_error.argtypes = [vp]
@@ -197,6 +202,30 @@ def _check(st, ctx=None):
 
 def dare_version():
     return lib().dare_version().decode()
+
+
+STATIC_MAX_ROW_BYTES = 8 << 20      # DARE_STATIC_MAX_ROW_BYTES
+STATIC_MAX_SCORE_ELEMS = 1 << 20    # DARE_STATIC_MAX_SCORE_ELEMS
+
+
+def dare_static_init(device=0):
+    _check(lib().dare_static_init(device), None)
+
+
+def dare_layer_step_static(wqkv_t, wo_t, n_heads, mode, threshold, hidden, q_prev, k_cache, v_cache, o_cache, out,
+                           reuse_mask, sel_idx=None, sel_count=None, scores=None, score_head=0, stream=None):
+    """dare_layer_step_static: the layer step without a context and without any allocation.
+    wqkv_t [3d, d] and wo_t [d, d] are the packed weights (dare_k_pack_weight)."""
+    import torch
+    batch, seq, d = hidden.shape
+    dtype = DARE_BF16 if hidden.dtype == torch.bfloat16 else DARE_F32
+    cfg = DareConfig(ctypes.sizeof(DareConfig), d, n_heads, d // n_heads, batch, seq, dtype, score_head,
+                     hidden.device.index or 0, 0)
+    st = lib().dare_layer_step_static(ctypes.byref(cfg), _ptr(wqkv_t), _ptr(wo_t), mode, threshold, batch, seq,
+                                      _ptr(hidden), _ptr(q_prev), _ptr(k_cache), _ptr(v_cache), _ptr(o_cache),
+                                      _ptr(out), _ptr(reuse_mask), _ptr(sel_idx), _ptr(sel_count), _ptr(scores),
+                                      _stream(stream))
+    _check(st, None)
 
 
 class DareLayer:

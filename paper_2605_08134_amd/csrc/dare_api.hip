@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -423,6 +424,129 @@ dare_status dare_layer_step(dare_ctx* ctx, int mode, float threshold, int batch,
   return step_impl(ctx, mode, threshold, batch, seq, hidden, q_prev, k_cache, v_cache, o_cache, out,
                    reuse_mask, sel_idx, sel_count, scores, BlockExtras{nullptr, nullptr}, hip_stream);
 }
+
+// ---------------------------------------------------------------------------
+// The layer step for callers that cannot allocate: no context, scratch in a file-scope
+// device array.
+// ---------------------------------------------------------------------------
+namespace {
+
+// Layout of the static scratch (bytes): queries | attention rows | fp32 scored query (up to
+// 8 k-range slabs) | refreshed-row list | per-sequence offsets.
+constexpr size_t kStaticRowBytes = DARE_STATIC_MAX_ROW_BYTES;          // batch * seq * hidden * sizeof(dtype)
+constexpr size_t kStaticScoreElems = DARE_STATIC_MAX_SCORE_ELEMS;     // fp32 elements of the scored query, slabs included
+constexpr size_t kStaticMaxTokens = kStaticRowBytes / (64 * 2);        // hidden >= 64, two bytes per element
+constexpr size_t kStaticOffQ = 0;
+constexpr size_t kStaticOffAttn = kStaticOffQ + kStaticRowBytes;
+constexpr size_t kStaticOffScore = kStaticOffAttn + kStaticRowBytes;
+constexpr size_t kStaticOffIdx = kStaticOffScore + kStaticScoreElems * sizeof(float);
+constexpr size_t kStaticOffOff = kStaticOffIdx + kStaticMaxTokens * sizeof(int32_t);
+constexpr size_t kStaticBytes = kStaticOffOff + (kStaticMaxTokens + 64) * sizeof(int32_t);
+static_assert(kStaticOffAttn % 256 == 0 && kStaticOffScore % 256 == 0 && kStaticOffIdx % 256 == 0 &&
+                  kStaticOffOff % 256 == 0, "scratch regions must stay aligned");
+
+}  // namespace
+
+// Every GPU the library runs on holds its own copy of this array until the process ends.  In
+// host code the name is only a handle: the memory is reached through the per-device address
+// that hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_lock;
+unsigned char* g_static_ptr[kMaxDevices];  // device address of `scratch` on each device, once looked up
+
+// The address of this device's copy of the scratch array (the device must be current).
+dare_status static_scratch(int device, unsigned char** out) {
+  if (device < 0 || device >= kMaxDevices) return fail(nullptr, DARE_ERR_INVALID_ARG, "device ordinal out of range");
+  std::lock_guard<std::mutex> lock(g_static_lock);
+  if (!g_static_ptr[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(nullptr, e, "hipGetSymbolAddress(scratch)");
+    if (!p) return fail(nullptr, DARE_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    g_static_ptr[device] = static_cast<unsigned char*>(p);
+  }
+  *out = g_static_ptr[device];
+  return DARE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+dare_status dare_static_init(int device) {
+  DeviceGuard guard;
+  hipError_t e = guard.enter(device);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "hipSetDevice");
+  unsigned char* p = nullptr;
+  return static_scratch(device, &p);
+}
+
+dare_status dare_layer_step_static(const dare_config* cfg, const void* wqkv_t, const void* wo_t, int mode,
+                                   float threshold, int batch, int seq, const void* hidden, float* q_prev,
+                                   void* k_cache, void* v_cache, void* o_cache, void* out, uint8_t* reuse_mask,
+                                   int32_t* sel_idx, int32_t* sel_count, float* scores, void* hip_stream) {
+  if (!cfg) return fail(nullptr, DARE_ERR_INVALID_ARG, "null config");
+  if (cfg->struct_size != sizeof(dare_config))
+    return fail(nullptr, DARE_ERR_INVALID_ARG, "struct_size does not match this library");
+  if (!wqkv_t || !wo_t) return fail(nullptr, DARE_ERR_INVALID_ARG, "null weight pointer");
+  if (cfg->flags != 0) return fail(nullptr, DARE_ERR_INVALID_ARG, "flags must be 0");
+  if (cfg->dtype != DARE_F32 && cfg->dtype != DARE_BF16) return fail(nullptr, DARE_ERR_INVALID_ARG, "unknown dtype");
+  if (cfg->hidden < 1 || cfg->n_heads < 1 || cfg->head_dim < 1 || cfg->device < 0)
+    return fail(nullptr, DARE_ERR_INVALID_ARG, "non-positive size");
+  if ((long)cfg->n_heads * cfg->head_dim != cfg->hidden)
+    return fail(nullptr, DARE_ERR_INVALID_ARG, "hidden != n_heads * head_dim");
+  if (cfg->score_head != 0 && cfg->score_head != -1)
+    return fail(nullptr, DARE_ERR_UNSUPPORTED, "score_head must be 0 or -1");
+  if (cfg->head_dim != 64 && cfg->head_dim != 128)
+    return fail(nullptr, DARE_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+  if (cfg->hidden % 64 != 0) return fail(nullptr, DARE_ERR_UNSUPPORTED, "hidden must be a multiple of 64");
+  if (batch < 1 || seq < 1) return fail(nullptr, DARE_ERR_INVALID_ARG, "batch and seq must be >= 1");
+  const size_t esize = cfg->dtype == DARE_BF16 ? 2 : 4;
+  const int score_width = cfg->score_head < 0 ? cfg->hidden : cfg->head_dim;
+  const size_t n_tok = (size_t)batch * (size_t)seq;
+  if (n_tok * (size_t)cfg->hidden * esize > kStaticRowBytes)
+    return fail(nullptr, DARE_ERR_UNSUPPORTED,
+                "batch * seq * hidden * sizeof(dtype) exceeds DARE_STATIC_MAX_ROW_BYTES, the static scratch");
+  if (n_tok * (size_t)score_width > kStaticScoreElems)
+    return fail(nullptr, DARE_ERR_UNSUPPORTED,
+                "batch * seq * scored width exceeds DARE_STATIC_MAX_SCORE_ELEMS, the static scratch");
+
+  DeviceGuard guard;
+  hipError_t e = guard.enter(cfg->device);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "hipSetDevice");
+  unsigned char* base = nullptr;
+  dare_status st = static_scratch(cfg->device, &base);
+  if (st != DARE_OK) return st;
+
+  // a context on the stack: the caller's packed weights, scratch inside the static array
+  dare_ctx c{};
+  c.cfg = *cfg;
+  c.cfg.max_batch = batch;
+  c.cfg.max_seq = seq;
+  c.esize = esize;
+  c.score_width = score_width;
+  c.wqkv_t = const_cast<void*>(wqkv_t);
+  c.wo_t = const_cast<void*>(wo_t);
+  c.q_buf = base + kStaticOffQ;
+  c.attn_buf = base + kStaticOffAttn;
+  c.q_new = reinterpret_cast<float*>(base + kStaticOffScore);
+  c.q_new_elems = kStaticScoreElems;
+  c.sel_idx = reinterpret_cast<int32_t*>(base + kStaticOffIdx);
+  c.sel_off = reinterpret_cast<int32_t*>(base + kStaticOffOff);
+  c.rule = DARE_RULE_SCORE;
+  st = check_step_args(&c, mode, threshold, batch, seq, hidden, q_prev, k_cache, v_cache, o_cache, out, reuse_mask);
+  if (st == DARE_OK)
+    st = step_impl(&c, mode, threshold, batch, seq, hidden, q_prev, k_cache, v_cache, o_cache, out, reuse_mask,
+                   sel_idx, sel_count, scores, BlockExtras{nullptr, nullptr}, hip_stream);
+  if (st != DARE_OK) g_create_err = c.err;
+  return st;
+}
+
+}  // extern "C"
 
 namespace {
 // (cos, sin) of pos * base^(-2 i / head_dim) in double precision, rounded to fp32
