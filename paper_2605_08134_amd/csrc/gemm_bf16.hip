@@ -133,13 +133,15 @@ __device__ __forceinline__ void store4(const GemmDev& p, float* c32, long tok, i
 
 // One output tile of C for m rows, computed by a team of WAVES_M * WAVES_N waves; tid
 // is the thread's index within the team and smem the team's own
-// smem_bytes<BM, BN, STAGES>() bytes.  A workgroup is one team (nsub = 1) or nsub teams
-// on neighbouring tiles (team number sub).  Teams share the workgroup barrier, so a
+// smem_bytes<BM, BN, STAGES>() bytes.  vblock is the workgroup's (virtual) block id: a
+// workgroup that walks several tiles calls this once per pass with block id + pass * grid
+// size; the result says whether that id held a tile.  A workgroup is one team (nsub = 1) or
+// nsub teams on neighbouring tiles (team number sub).  Teams share the workgroup barrier, so a
 // team without a tile of its own repeats the last tile and stores nothing.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
-__device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigned char* smem,
-                                          const int tid, const int sub = 0, const int nsub = 1,
-                                          lds_idx_t lidx = nullptr) {
+__device__ __forceinline__ bool gemm_tile(const GemmDev& p, const int m, unsigned char* smem,
+                                          const int tid, const int vblock, const int sub = 0,
+                                          const int nsub = 1, lds_idx_t lidx = nullptr) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -158,10 +160,10 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
   const int total = tiles_m * tiles_n * parts;
   const int blocks = (total + nsub - 1) / nsub;
   const int per_xcd = (blocks + 7) >> 3;
-  const int slot = blockIdx.x >> 3;
-  if (slot >= per_xcd) return;
-  const int blk = (blockIdx.x & 7) * per_xcd + slot;
-  if (blk >= blocks) return;
+  const int slot = vblock >> 3;
+  if (slot >= per_xcd) return false;
+  const int blk = (vblock & 7) * per_xcd + slot;
+  if (blk >= blocks) return false;
   int unit = blk * nsub + sub;
   const bool live = unit < total;
   unit = live ? unit : total - 1;
@@ -351,6 +353,7 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
       }
     }
   }
+  return true;
 }
 
 // The same tile with v_mfma_f32_16x16x32_bf16: wave tiles in units of 16, so that 8 waves can
@@ -361,8 +364,8 @@ __device__ __forceinline__ void gemm_tile(const GemmDev& p, const int m, unsigne
 // two such slices, and all fragments of the next k-step are fetched under the MFMAs of the
 // current one.  No teams, no k-parts.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
-__device__ __forceinline__ void gemm_tile16(const GemmDev& p, const int m, unsigned char* smem, const int tid,
-                                            lds_idx_t lidx = nullptr) {
+__device__ __forceinline__ bool gemm_tile16(const GemmDev& p, const int m, unsigned char* smem, const int tid,
+                                            const int vblock, lds_idx_t lidx = nullptr) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 16, TN = WN / 16;
@@ -376,10 +379,10 @@ __device__ __forceinline__ void gemm_tile16(const GemmDev& p, const int m, unsig
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
   const int total = tiles_m * tiles_n;
   const int per_xcd = (total + 7) >> 3;
-  const int slot = blockIdx.x >> 3;
-  if (slot >= per_xcd) return;
-  const int unit = (blockIdx.x & 7) * per_xcd + slot;
-  if (unit >= total) return;
+  const int slot = vblock >> 3;
+  if (slot >= per_xcd) return false;
+  const int unit = (vblock & 7) * per_xcd + slot;
+  if (unit >= total) return false;
   const int group_size = GROUP_M * tiles_n;
   const int first_m = (unit / group_size) * GROUP_M;
   const int rows_in_group = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
@@ -497,6 +500,7 @@ __device__ __forceinline__ void gemm_tile16(const GemmDev& p, const int m, unsig
       store4(p, p.c32, tok_out[i], col, acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
     }
   }
+  return true;
 }
 
 // ---- very few rows (at most 16 TMS): a stream over the weight matrix ------------------
@@ -578,7 +582,7 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDe
   __shared__ __attribute__((aligned(1024))) unsigned char smem[smem_bytes<BM, BN, STAGES>()];
   const int m = p.m_dev ? *p.m_dev : p.m_max;
   if (m <= 0) return;
-  gemm_tile<BM, BN, WAVES_M, WAVES_N, STAGES>(p, m, smem, threadIdx.x);
+  gemm_tile<BM, BN, WAVES_M, WAVES_N, STAGES>(p, m, smem, threadIdx.x, blockIdx.x);
 }
 
 // ---- row count read on the device: the tile shape follows it -------------------------
@@ -595,6 +599,7 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64) gemm_bf16_kernel(GemmDe
 //   waves, beyond that.
 constexpr int kWideSmem = smem_bytes<128, 128, 4>();
 constexpr int kWideBigTiles = 160, kWideSingle = 256, kWideFullTiles = 200;
+constexpr int kWideGrid = 256;  // workgroups of a launch: one per CU
 __host__ __device__ inline int tiles_of(int m, int n, int bm, int bn) {
   return ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
 }
@@ -604,7 +609,7 @@ __host__ __device__ inline bool one_round(int tiles) { return tiles >= 192 && ti
 // folded into the first kernel that needs the list: a compaction kernel of its own costs a
 // launch, 4-5 us of a 90 us step, for a few hundred bytes of work).  512 threads, up to
 // kSelMaxTokens tokens, four per thread; ascending by construction.  Returns the count.
-__device__ __forceinline__ int derive_rows(const GemmDev& p, int32_t* list, int* wave_tot) {
+__device__ __forceinline__ int derive_rows(const GemmDev& p, int32_t* list, int* wave_tot, bool publish) {
   const int n_tok = p.sel_batch * p.sel_seq;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = tid * 4;
@@ -633,7 +638,7 @@ __device__ __forceinline__ int derive_rows(const GemmDev& p, int32_t* list, int*
   for (int k = 0; k < 4; ++k)
     if (z[k]) list[rank++] = t0 + k;
   __syncthreads();
-  if (blockIdx.x == 0) {  // what the compaction kernel would have written, for the kernels that follow
+  if (publish && blockIdx.x == 0) {  // what the compaction kernel would have written, for the kernels that follow
     for (int r = tid; r < total; r += 512) {
       p.sel_idx_out[r] = list[r];
       if (p.sel_idx_out2) p.sel_idx_out2[r] = list[r];
@@ -657,12 +662,15 @@ __device__ __forceinline__ int derive_rows(const GemmDev& p, int32_t* list, int*
   return total;
 }
 
+// FUSED: the row list is derived from the mask bytes inside the kernel (two instantiations,
+// so that the plain one carries none of the list handling).
+template <bool FUSED>
 __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kWideSmem];
   // a row list derived from the mask lives at the start of the stage memory until every
   // thread has taken the entries it needs (gemm_tile / skinny_tile read them before their
-  // first load into LDS); a workgroup that allocates more than 128 KiB of LDS was measured
-  // 20 % slower on this chip, so the list gets no memory of its own
+  // first load into LDS): the list gets no memory of its own, and a workgroup that walks
+  // several tiles derives it again in front of every further pass
   static_assert(kSelMaxTokens * 4 + 64 <= kWideSmem, "row list must fit the stage memory");
   // (the list starts 64 bytes in: LDS offset 0 is the null pointer of the LDS address space,
   // and gemm_tile takes "no list" as a null pointer)
@@ -670,12 +678,13 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   int32_t* sel_list = reinterpret_cast<int32_t*>(smem + 64);
   static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem &&
                     smem_bytes<128, 192, 3>() <= kWideSmem && smem_bytes<128, 96, 4>() <= kWideSmem &&
-                    smem_bytes<128, 48, 5>() <= kWideSmem && smem_bytes<128, 64, 4>() <= kWideSmem,
+                    smem_bytes<128, 48, 5>() <= kWideSmem && smem_bytes<128, 64, 4>() <= kWideSmem &&
+                    smem_bytes<256, 192, 2>() <= kWideSmem,
                 "shared buffer too small");
   int m;
   lds_idx_t lidx = nullptr;
-  if (p.sel_mask) {
-    m = derive_rows(p, sel_list, sel_wave_tot);
+  if constexpr (FUSED) {
+    m = derive_rows(p, sel_list, sel_wave_tot, true);
     lidx = (lds_idx_t)sel_list;
   } else {
     m = p.m_dev ? *p.m_dev : p.m_max;
@@ -689,31 +698,44 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
     if (m <= 16) skinny_tile<8, 1>(p, m, smem, threadIdx.x, lidx); else skinny_tile<8, 2>(p, m, smem, threadIdx.x, lidx);
     return;
   }
+  // The grid is one workgroup per CU whatever the count turns out to be (a grid sized for the
+  // worst case, whose surplus workgroups return at once, costs 1 us more at 205 rows); shapes
+  // that can have more tiles than that walk them in passes, virtual block id = block id +
+  // pass * grid size.  Every thread of the workgroup sees the same m and so takes the same
+  // branch and the same number of passes.
+  auto passes = [&](auto tile) __attribute__((always_inline)) {
+    for (int vb = blockIdx.x;; vb += gridDim.x) {
+      if (vb != (int)blockIdx.x) {
+        __syncthreads();  // the ring is reused: everybody is done with the last tile
+        if constexpr (FUSED) derive_rows(p, sel_list, sel_wave_tot, false);
+      }
+      if (!tile(vb)) break;
+    }
+  };
   if (p.n % 256 == 0 && tiles_of(m, p.n, 256, 256) >= 2 * kWideSingle) {
-    gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x, 0, 1, lidx);
+    passes([&](int vb) { return gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x, vb, 0, 1, lidx); });
   } else if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
-    gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x, 0, 1, lidx);
+    passes([&](int vb) { return gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x, vb, 0, 1, lidx); });
   } else if (p.n % 192 == 0 && one_round(tiles_of(m, p.n, 128, 192))) {
-    gemm_tile16<128, 192, 4, 2, 3>(p, m, smem, threadIdx.x, lidx);
+    gemm_tile16<128, 192, 4, 2, 3>(p, m, smem, threadIdx.x, blockIdx.x, lidx);  // (at most one tile per workgroup)
   } else if (m > 64 && p.n % 48 == 0 && one_round(tiles_of(m, p.n, 128, 48))) {
-    gemm_tile16<128, 48, 8, 1, 5>(p, m, smem, threadIdx.x, lidx);
+    gemm_tile16<128, 48, 8, 1, 5>(p, m, smem, threadIdx.x, blockIdx.x, lidx);
   } else if (m > 128 && one_round(tiles_of(m, p.n, 128, 64))) {
-    gemm_tile16<128, 64, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
-
+    gemm_tile16<128, 64, 4, 2, 4>(p, m, smem, threadIdx.x, blockIdx.x, lidx);
   } else if (p.n % 96 == 0 && one_round(tiles_of(m, p.n, 128, 96))) {
-    gemm_tile16<128, 96, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
+    gemm_tile16<128, 96, 4, 2, 4>(p, m, smem, threadIdx.x, blockIdx.x, lidx);
   } else if (tiles_of(m, p.n, 128, 128) >= kWideBigTiles) {
-    gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x, 0, 1, lidx);
+    passes([&](int vb) { return gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x, vb, 0, 1, lidx); });
+  } else if (tiles_of(m, p.n, 64, 64) <= kWideSingle) {
+    // one tile per workgroup: all eight waves on it (16 x 32 each with the 16-wide MFMA
+    // shape; measured 19.2 against 21.1 us for four waves of 32 x 32 at 205 rows, n = 4096)
+    gemm_tile16<64, 64, 4, 2, 4>(p, m, smem, threadIdx.x, blockIdx.x, lidx);
   } else {
     const int team = threadIdx.x >> 8;
-    const int teams = tiles_of(m, p.n, 64, 64) > kWideSingle ? 2 : 1;
-    if (teams == 1) {
-      // one tile per workgroup: all eight waves on it (16 x 32 each with the 16-wide MFMA
-      // shape; measured 19.2 against 21.1 us for four waves of 32 x 32 at 205 rows, n = 4096)
-      gemm_tile16<64, 64, 4, 2, 4>(p, m, smem, threadIdx.x, lidx);
-      return;
-    }
-    gemm_tile<64, 64, 2, 2, 4>(p, m, smem + team * smem_bytes<64, 64, 4>(), threadIdx.x & 255, team, teams, lidx);
+    passes([&](int vb) {
+      return gemm_tile<64, 64, 2, 2, 4>(p, m, smem + team * smem_bytes<64, 64, 4>(), threadIdx.x & 255, vb, team, 2,
+                                        lidx);
+    });
   }
 }
 
@@ -768,9 +790,10 @@ hipError_t launch_fixed(const GemmArgs& g, hipStream_t s) {
 }
 
 hipError_t launch_rows_wide(const GemmArgs& g, hipStream_t s) {
-  // worst case over the row counts 1 .. m_max of the blocks any of the shapes needs;
-  // the 64 x 64 shape is only chosen below kWideBigTiles 128 x 128 tiles, each of which
-  // holds at most four small ones
+  // worst case over the row counts 1 .. m_max of the blocks any of the shapes needs (the
+  // 64 x 64 shape is only chosen below kWideBigTiles 128 x 128 tiles, each of which holds
+  // at most four small ones), capped at one workgroup per CU: shapes with more tiles than
+  // that walk them in passes
   const int small = tiles_of(g.m_max, g.n, 64, 64);
   int pairs = (small + 1) / 2;
   const int pairs_cap = (4 * (kWideBigTiles - 1) + 1) / 2;
@@ -779,7 +802,11 @@ hipError_t launch_rows_wide(const GemmArgs& g, hipStream_t s) {
   const int big = tiles_of(g.m_max, g.n, 128, 128);
   if (big >= kWideBigTiles && big > blocks) blocks = big;
   if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(gemm_bf16_rows_wide_kernel, dim3(grid_for(blocks)), dim3(512), 0, s, to_dev(g));
+  if (blocks > kWideGrid) blocks = kWideGrid;
+  if (g.sel_mask)
+    hipLaunchKernelGGL(gemm_bf16_rows_wide_kernel<true>, dim3(grid_for(blocks)), dim3(512), 0, s, to_dev(g));
+  else
+    hipLaunchKernelGGL(gemm_bf16_rows_wide_kernel<false>, dim3(grid_for(blocks)), dim3(512), 0, s, to_dev(g));
   return hipGetLastError();
 }
 

@@ -163,6 +163,25 @@ def test_more_sequences_than_threads_in_the_fused_row_list():
     gl.layer.destroy()
 
 
+def test_refreshed_rows_beyond_one_pass_of_the_grid():
+    """2 x 1024 tokens, all of them refreshed, hidden 2048: the refreshed-row projection of the KV
+    mode (2048 rows x 4096 columns in 128 x 128 tiles = 512 tiles) takes two passes of its 256
+    workgroups and derives its row list from the mask again in front of the second."""
+    case = synth.make_case("llada8b", seed=93, batch=2, seq=1024, hidden=2048, n_heads=16, head_dim=128,
+                           fraction=1.0)
+    state = pu.oracle_fill(case)
+    gl = pu.GpuLayer(case)
+    for mode in (orc.MODE_KV, orc.MODE_KVO):
+        info, got, want = _run(case, gl, state, mode, synth.TAU_SEPARATING)
+        assert int(got["sel_count"].sum()) == 2048
+    # and with a third of the rows kept: rows gathered through the list in both passes
+    case = dict(case, **synth.make_hidden_pair(94, 2, 1024, 2048, 0.66, "bf16"))     # same weights, other rows
+    state = pu.oracle_fill(case)
+    info, got, want = _run(case, gl, state, orc.MODE_KV, synth.TAU_SEPARATING)
+    assert int(got["sel_count"].sum()) == 2 * 676
+    gl.layer.destroy()
+
+
 # ------------------------------------------------------------------ LLaDA-8B-shaped layer, full size
 class _Llada:
     """One GPU layer with the LLaDA-8B-shaped weights of seed 1234 and, per perturbed fraction,
