@@ -96,10 +96,10 @@ def main():
     def time_mode(mode, xa, xb, steps, warmup):
         state = layer.new_state(Bn, T)
         fill(state, xa)
-        # set-up: 20 steps that bring clocks and caches to their running state (the dense leg needs
-        # them as much as the reuse leg: its first steps after an idle gap run 10-15 % slow), then
+        # set-up: 100 steps that bring clocks and caches to their running state (the first tens of
+        # steps after an idle gap run 10-15 % slow, the dense leg's more than the reuse leg's), then
         # the W warm-up steps proper; an even count, so that the next step sees xb again
-        run_steps(mode, xa, xb, state, 20 + warmup + (warmup % 2))
+        run_steps(mode, xa, xb, state, 100 + warmup + (warmup % 2))
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
@@ -153,7 +153,7 @@ def main():
         for _ in range(n):
             B.dare_k_gemm(xb.view(Bn * T, d), wqkv_t, qkv_out, d, idx=idx, m_dev=m_dev, m_max=Bn * T)
 
-    dominant(50)
+    dominant(300)          # clocks at their running state (the first hundreds of launches run 10 % slow)
     torch.cuda.synchronize()
     n_dom = 200
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
