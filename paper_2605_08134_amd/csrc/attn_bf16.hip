@@ -93,7 +93,7 @@ __device__ __forceinline__ void attn_block(const AttnDev& p, int b, int h, int q
   static_assert(LPW * (NST - 1) < 64, "vmcnt range");
 
   const int T = p.seq;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (a scalar: M0 addressing)
   const int qw = wave % QW, kw = wave / QW;
   const int l32 = lane & 31, half = lane >> 5;
 

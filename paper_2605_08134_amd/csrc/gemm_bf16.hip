@@ -176,7 +176,9 @@ __device__ __forceinline__ bool gemm_tile(const GemmDev& p, const int m, unsigne
   const int tile_n = rem / rows_in_group;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int lane = tid & 63, wave = tid >> 6;
+  // (the wave number as a scalar: LDS addresses of the global -> LDS loads go through M0, and a
+  // wave number held in a vector register would send every one of them through v_readfirstlane)
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
   const int l32 = lane & 31, half = lane >> 5;
 
@@ -363,7 +365,7 @@ __device__ __forceinline__ bool gemm_tile(const GemmDev& p, const int m, unsigne
 // gemm_tile; a fragment is 16 rows x 32 k (lane L: row L & 15, k-chunk L >> 4), a k-step holds
 // two such slices, and all fragments of the next k-step are fetched under the MFMAs of the
 // current one.  No teams, no k-parts.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool PAIRED = false>
 __device__ __forceinline__ bool gemm_tile16(const GemmDev& p, const int m, unsigned char* smem, const int tid,
                                             const int vblock, lds_idx_t lidx = nullptr) {
   constexpr int NW = WAVES_M * WAVES_N;
@@ -390,7 +392,9 @@ __device__ __forceinline__ bool gemm_tile16(const GemmDev& p, const int m, unsig
   const int tile_m = first_m + rem % rows_in_group, tile_n = rem / rows_in_group;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int lane = tid & 63, wave = tid >> 6;
+  // (the wave number as a scalar: LDS addresses of the global -> LDS loads go through M0, and a
+  // wave number held in a vector register would send every one of them through v_readfirstlane)
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
   const int l16 = lane & 15, kq = lane >> 4;
   const int KT = p.k / BK;
@@ -464,28 +468,63 @@ __device__ __forceinline__ bool gemm_tile16(const GemmDev& p, const int m, unsig
     }
   };
 
+  if constexpr (!PAIRED) {
 #pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) issue_loads(s < KT ? s : KT - 1, s);
-  wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
-  load_frags(0, 0);
-  auto kstep = [&](int kt, auto set_c) __attribute__((always_inline)) {
-    constexpr int SET = decltype(set_c)::value;
-    const int nxt = kt + STAGES - 1;
-    issue_loads(nxt < KT ? nxt : KT - 1, nxt % STAGES);
-    mma(SET, 0, PRE);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int s = 0; s < STAGES - 1; ++s) issue_loads(s < KT ? s : KT - 1, s);
     wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
-    load_frags((kt + 1) % STAGES, SET ^ 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(SET, PRE, NMMA);
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  int kt = 0;
-  for (; kt + 1 < KT; kt += 2) {
-    kstep(kt, std::integral_constant<int, 0>{});
-    kstep(kt + 1, std::integral_constant<int, 1>{});
+    load_frags(0, 0);
+    auto kstep = [&](int kt, auto set_c) __attribute__((always_inline)) {
+      constexpr int SET = decltype(set_c)::value;
+      const int nxt = kt + STAGES - 1;
+      issue_loads(nxt < KT ? nxt : KT - 1, nxt % STAGES);
+      mma(SET, 0, PRE);
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vmcnt_and_barrier<LPW*(STAGES - 2)>();
+      load_frags((kt + 1) % STAGES, SET ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(SET, PRE, NMMA);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt + 1 < KT; kt += 2) {
+      kstep(kt, std::integral_constant<int, 0>{});
+      kstep(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
+  } else {
+    // Two k-steps per barrier (small tiles, whose k-step holds too few MFMAs to carry a
+    // barrier of its own): the ring is filled and drained in pairs of stages.  The barrier
+    // that ends an odd k-step kt lets stages kt+1 and kt+2 be read and the slots of kt-1 and
+    // kt be refilled; the even k-step after it issues the loads of stages kt+STAGES-2 and
+    // kt+STAGES-1 into those two slots and reads stage kt+1 without a barrier.
+    static_assert(STAGES % 2 == 0 && STAGES >= 4, "paired ring");
+    static_assert(LPW * (STAGES - 2) < 64, "vmcnt range");
+#pragma unroll
+    for (int s = 0; s < STAGES - 2; ++s) issue_loads(s < KT ? s : KT - 1, s);
+    wait_vmcnt_and_barrier<LPW*(STAGES - 4)>();
+    load_frags(0, 0);
+    auto kstep = [&](int kt, auto set_c) __attribute__((always_inline)) {
+      constexpr int SET = decltype(set_c)::value;
+      if constexpr (SET == 0) {
+        const int n0s = kt + STAGES - 2, n1s = kt + STAGES - 1;
+        issue_loads(n0s < KT ? n0s : KT - 1, n0s % STAGES);
+        issue_loads(n1s < KT ? n1s : KT - 1, n1s % STAGES);
+      }
+      mma(SET, 0, PRE);
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (SET == 1) wait_vmcnt_and_barrier<LPW*(STAGES - 4)>();
+      load_frags((kt + 1) % STAGES, SET ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(SET, PRE, NMMA);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt + 1 < KT; kt += 2) {
+      kstep(kt, std::integral_constant<int, 0>{});
+      kstep(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
   }
-  if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
   wait_vmcnt<0>();
 
   // acc[i][j][e] = C[row, col]: row = m0 + wave_m*WM + 16 i + l16, col = n0 + wave_n*WN + 16 j + 4 kq + e
@@ -516,7 +555,9 @@ template <int NW, int TMS>
 __device__ __forceinline__ void skinny_tile(const GemmDev& p, const int m, unsigned char* smem, const int tid,
                                             lds_idx_t lidx = nullptr) {
   constexpr int UNR = TMS == 1 ? 16 : 8;
-  const int lane = tid & 63, wave = tid >> 6;
+  // (the wave number as a scalar: LDS addresses of the global -> LDS loads go through M0, and a
+  // wave number held in a vector register would send every one of them through v_readfirstlane)
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, kq = lane >> 4;
   const int groups = p.n >> 4;
   const int steps = p.k >> 5;
@@ -676,7 +717,8 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
   // and gemm_tile takes "no list" as a null pointer)
   int* sel_wave_tot = reinterpret_cast<int*>(smem);
   int32_t* sel_list = reinterpret_cast<int32_t*>(smem + 64);
-  static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<256, 256, 2>() <= kWideSmem &&
+  static_assert(2 * smem_bytes<64, 64, 4>() <= kWideSmem && smem_bytes<64, 64, 8>() <= kWideSmem &&
+                    smem_bytes<256, 256, 2>() <= kWideSmem &&
                     smem_bytes<128, 192, 3>() <= kWideSmem && smem_bytes<128, 96, 4>() <= kWideSmem &&
                     smem_bytes<128, 48, 5>() <= kWideSmem && smem_bytes<128, 64, 4>() <= kWideSmem &&
                     smem_bytes<256, 192, 2>() <= kWideSmem,
@@ -728,8 +770,10 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
     passes([&](int vb) { return gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x, vb, 0, 1, lidx); });
   } else if (tiles_of(m, p.n, 64, 64) <= kWideSingle) {
     // one tile per workgroup: all eight waves on it (16 x 32 each with the 16-wide MFMA
-    // shape; measured 19.2 against 21.1 us for four waves of 32 x 32 at 205 rows, n = 4096)
-    gemm_tile16<64, 64, 4, 2, 4>(p, m, smem, threadIdx.x, blockIdx.x, lidx);
+    // shape; measured 19.2 against 21.1 us for four waves of 32 x 32 at 205 rows, n = 4096),
+    // the whole stage memory as a ring of eight stages with one barrier per two k-steps
+    // (0.3-0.6 us less than four stages and a barrier per k-step at 40-256 rows, n = 4096)
+    gemm_tile16<64, 64, 4, 2, 8, true>(p, m, smem, threadIdx.x, blockIdx.x, lidx);
   } else {
     const int team = threadIdx.x >> 8;
     passes([&](int vb) {
