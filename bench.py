@@ -624,6 +624,16 @@ def measured_peaks(torch, B, dev, d):
                 flops[0] = B.dare_bench_mfma_loop(2048, 4096, pattern)
         us = _time_us(torch, run, 5, warm=2)
         res[key] = flops[0] / (us * 1e-6) / 1e12
+    # what one CU pulls from memory into LDS when 8 .. 256 CUs pull at once (every workgroup
+    # walks 12 MiB of its own, 3 GiB in all at 256: nothing is re-read)
+    per_block = 12 << 20
+    big = torch.ones(((256 * per_block) // 4,), dtype=torch.int32, device=dev)
+    res["stream_to_lds_GBs_per_cu"] = {}
+    for n_blocks in (8, 32, 64, 128, 256):
+        us = _time_us(torch, lambda n, nb=n_blocks: [B.dare_bench_stream(nb, per_block, 2, big) for _ in range(n)],
+                      3, warm=1)
+        res["stream_to_lds_GBs_per_cu"][str(n_blocks)] = per_block / (us * 1e-6) / 1e9
+    del big
     return res
 
 

@@ -21,6 +21,19 @@ extern "C" {
 int dare_bench_mfma_loop(int n_blocks, int n_iter, int pattern, float* out, double* flops,
                          void* hip_stream);
 
+/*
+ * Enqueues n_blocks workgroups of 8 waves; workgroup b reads src[b * bytes_per_block ..
+ * (b + 1) * bytes_per_block) once, front to back, with global -> LDS loads of 16 bytes per
+ * lane, `depth` (1, 2 or 4) batches of 64 KiB per workgroup in flight.  src (device) must
+ * hold n_blocks * bytes_per_block bytes; bytes_per_block is a multiple of 64 KiB.  out
+ * (device, may be NULL) is never written in practice.  Time the launch with events:
+ * bytes_per_block / time is what one CU pulls when n_blocks CUs pull at once (one
+ * workgroup per CU while n_blocks is at most the CU count).  Returns 0, 1 (bad argument) or
+ * 4 (launch failed).
+ */
+int dare_bench_stream(int n_blocks, unsigned long long bytes_per_block, int depth, const void* src,
+                      unsigned* out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

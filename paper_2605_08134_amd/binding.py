@@ -510,7 +510,7 @@ def dare_k_copy_rows(src, dst, idx=None, m_dev=None, stream=None):
 # ---- benchmark aids (libdare_bench.so, include/dare_bench.h) ------------------------------
 
 BENCH_LIB_PATH = os.path.join(PKG_DIR, "libdare_bench.so")
-BENCH_EXPORTS = ("dare_bench_mfma_loop",)
+BENCH_EXPORTS = ("dare_bench_mfma_loop", "dare_bench_stream")
 _bench_lib = None
 
 
@@ -523,8 +523,21 @@ def bench_lib():
         L.dare_bench_mfma_loop.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double),
                                                                 ctypes.c_void_p]
         L.dare_bench_mfma_loop.restype = ctypes.c_int
+        L.dare_bench_stream.argtypes = [ctypes.c_int, ctypes.c_ulonglong, ctypes.c_int, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_void_p]
+        L.dare_bench_stream.restype = ctypes.c_int
         _bench_lib = L
     return _bench_lib
+
+
+def dare_bench_stream(n_blocks, bytes_per_block, depth, src, stream=None):
+    """Enqueue the one-workgroup-per-CU stream over src (a device tensor of at least
+    n_blocks * bytes_per_block bytes)."""
+    if src.numel() * src.element_size() < n_blocks * bytes_per_block:
+        raise ValueError("source buffer too small")
+    st = bench_lib().dare_bench_stream(n_blocks, bytes_per_block, depth, _ptr(src), None, _stream(stream))
+    if st != 0:
+        raise DareError(st, "dare_bench_stream failed")
 
 
 def dare_bench_mfma_loop(n_blocks, n_iter, pattern, stream=None):
