@@ -124,8 +124,21 @@ def _long_k_operands(n):
 
 @pytest.mark.parametrize("n,count,shape", [
     (1024, 1100, "64 x 64, two tiles per workgroup"),
+    (4096, 16, "register-fed stream, one row block, full"),
+    (4096, 17, "register-fed stream, two row blocks, one row in the second"),
     (4096, 24, "register-fed stream, two row blocks"),
+    (4096, 32, "register-fed stream, two full row blocks"),
+    (4096, 33, "64 x 64 on the paired ring, one row tile"),
+    (4096, 64, "64 x 64 on the paired ring, one full row tile"),
+    (4096, 65, "64 x 64 on the paired ring, one row in the second row tile"),
+    (4096, 205, "64 x 64 on the paired ring, four row tiles"),
+    (4096, 256, "64 x 64 on the paired ring, 256 tiles"),
+    (4096, 257, "128 x 64, one row in the third row tile"),
     (4096, 400, "128 x 64"),
+    (12288, 64, "64 x 64, one tile per workgroup, full row tile"),
+    (12288, 65, "128 x 48, one row beyond 64"),
+    (12288, 128, "128 x 48, full row tile"),
+    (12288, 129, "128 x 96, one row in the second row tile"),
     (12288, 24, "64 x 64, one tile per workgroup"),
     (12288, 100, "128 x 48"),
     (12288, 205, "128 x 96"),
