@@ -131,6 +131,18 @@ __device__ __forceinline__ void store4(const GemmDev& p, float* c32, long tok, i
   *reinterpret_cast<bf16x4*>(cbase + tok * p.ldc + (col - seg * p.seg_n)) = o;
 }
 
+// Tile order: GROUP_M row-tiles per column step (the tiles that run at the same time on one
+// XCD then share few distinct A and W tiles).
+__device__ __forceinline__ void tile_of_unit(const int unit, const int tiles_m, const int tiles_n, int& tile_m,
+                                             int& tile_n) {
+  const int group_size = GROUP_M * tiles_n;
+  const int first_m = (unit / group_size) * GROUP_M;
+  const int rows_in_group = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+  const int rem = unit % group_size;
+  tile_m = first_m + rem % rows_in_group;
+  tile_n = rem / rows_in_group;
+}
+
 // One output tile of C for m rows, computed by a team of WAVES_M * WAVES_N waves; tid
 // is the thread's index within the team and smem the team's own
 // smem_bytes<BM, BN, STAGES>() bytes.  vblock is the workgroup's (virtual) block id: a
@@ -141,7 +153,8 @@ __device__ __forceinline__ void store4(const GemmDev& p, float* c32, long tok, i
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 __device__ __forceinline__ bool gemm_tile(const GemmDev& p, const int m, unsigned char* smem,
                                           const int tid, const int vblock, const int sub = 0,
-                                          const int nsub = 1, lds_idx_t lidx = nullptr) {
+                                          const int nsub = 1, lds_idx_t lidx = nullptr,
+                                          const int forced_tile_m = -1, const int forced_tile_n = 0) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -157,23 +170,26 @@ __device__ __forceinline__ bool gemm_tile(const GemmDev& p, const int m, unsigne
   // in this order)
   const int parts = p.k_parts;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
-  const int total = tiles_m * tiles_n * parts;
-  const int blocks = (total + nsub - 1) / nsub;
-  const int per_xcd = (blocks + 7) >> 3;
-  const int slot = vblock >> 3;
-  if (slot >= per_xcd) return false;
-  const int blk = (vblock & 7) * per_xcd + slot;
-  if (blk >= blocks) return false;
-  int unit = blk * nsub + sub;
-  const bool live = unit < total;
-  unit = live ? unit : total - 1;
-  const int logical = unit / parts, part = unit - logical * parts;
-  const int group_size = GROUP_M * tiles_n;
-  const int first_m = (logical / group_size) * GROUP_M;
-  const int rows_in_group = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
-  const int rem = logical % group_size;
-  const int tile_m = first_m + rem % rows_in_group;
-  const int tile_n = rem / rows_in_group;
+  int tile_m, tile_n, part = 0;
+  bool live = true;
+  if (forced_tile_m >= 0) {  // the caller names the tile (whole k, one tile for all waves)
+    tile_m = forced_tile_m;
+    tile_n = forced_tile_n;
+  } else {
+    const int total = tiles_m * tiles_n * parts;
+    const int blocks = (total + nsub - 1) / nsub;
+    const int per_xcd = (blocks + 7) >> 3;
+    const int slot = vblock >> 3;
+    if (slot >= per_xcd) return false;
+    const int blk = (vblock & 7) * per_xcd + slot;
+    if (blk >= blocks) return false;
+    int unit = blk * nsub + sub;
+    live = unit < total;
+    unit = live ? unit : total - 1;
+    const int logical = unit / parts;
+    part = unit - logical * parts;
+    tile_of_unit(logical, tiles_m, tiles_n, tile_m, tile_n);
+  }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   // (the wave number as a scalar: LDS addresses of the global -> LDS loads go through M0, and a
@@ -755,7 +771,43 @@ __global__ void __launch_bounds__(512) gemm_bf16_rows_wide_kernel(GemmDev p) {
     }
   };
   if (p.n % 256 == 0 && tiles_of(m, p.n, 256, 256) >= 2 * kWideSingle) {
-    passes([&](int vb) { return gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x, vb, 0, 1, lidx); });
+    // Rounds of 256 x 256 tiles; when the last round would be at most half full (624 tiles on
+    // 256 workgroups: 256 + 256 + 112), its tiles are cut into four 128 x 128 tiles each and
+    // spread over all workgroups (one or two short rounds instead of a long, mostly idle one).
+    // Virtual block ids: 8 per XCD slot, as gemm_tile decodes them.
+    const int G = gridDim.x;
+    const int tiles_m = (m + 255) / 256, tiles_n = p.n / 256;
+    const int total = tiles_m * tiles_n, per_xcd = (total + 7) >> 3;
+    const int n_vb = per_xcd * 8;
+    const int last = n_vb % G;
+    const bool cut = n_vb > G && last > 0 && 2 * last <= G;
+    const int whole_end = cut ? n_vb - last : n_vb;
+    bool first = true;
+    auto next_tile = [&]() __attribute__((always_inline)) {
+      if (!first) {
+        __syncthreads();  // the ring is reused: everybody is done with the last tile
+        if constexpr (FUSED) derive_rows(p, sel_list, sel_wave_tot, false);
+      }
+      first = false;
+    };
+    for (int vb = blockIdx.x; vb < whole_end; vb += G) {
+      next_tile();
+      gemm_tile<256, 256, 2, 4, 2>(p, m, smem, threadIdx.x, vb, 0, 1, lidx);
+    }
+    if (cut) {
+      // child c: the parents of an XCD slot stay on their XCD (c & 7), 4 children per parent
+      for (int c = blockIdx.x; c < 4 * last; c += G) {
+        const int vb = whole_end + ((c >> 5) << 3) + (c & 7), quarter = (c >> 3) & 3;
+        const int unit = (vb & 7) * per_xcd + (vb >> 3);
+        if (unit >= total) continue;
+        int tm, tn;
+        tile_of_unit(unit, tiles_m, tiles_n, tm, tn);
+        const int cm = 2 * tm + (quarter >> 1), cn = 2 * tn + (quarter & 1);
+        if (cm * 128 >= m) continue;
+        next_tile();
+        gemm_tile<128, 128, 4, 2, 4>(p, m, smem, threadIdx.x, 0, 0, 1, lidx, cm, cn);
+      }
+    }
   } else if (p.n % 192 == 0 && tiles_of(m, p.n, 256, 192) >= kWideFullTiles) {
     passes([&](int vb) { return gemm_tile<256, 192, 4, 2, 2>(p, m, smem, threadIdx.x, vb, 0, 1, lidx); });
   } else if (p.n % 192 == 0 && one_round(tiles_of(m, p.n, 128, 192))) {

@@ -82,11 +82,14 @@ def test_gemm_selected_rows_device_count(B, dtype, count):
 
 
 @pytest.mark.parametrize("n_tok,count", [(1024, 0), (1024, 1), (1024, 7), (1024, 16), (1024, 17), (1024, 32), (1024, 33), (1024, 52), (1024, 100), (1024, 205),
-                                         (1024, 700), (1024, 1024), (3072, 2900)])
+                                         (1024, 700), (1024, 1024), (3072, 2900), (4096, 2561), (4096, 3266),
+                                         (4096, 3500)])
 def test_gemm_selected_rows_wide_output(B, n_tok, count):
     """Wide outputs (n >= 8192) take the 8-wave kernel, whose tile shape follows the
     device-side row count: one 64 x 64 tile per workgroup, two, 128 x 128, 256 x 192,
-    256 x 256."""
+    256 x 256 in rounds over 256 workgroups.  2561, 2900 and 3266 rows leave a last round that
+    is at most half full and is cut into 128 x 128 tiles (64, 256 and 448 of them, some
+    without rows); 3500 rows walk three rounds of whole tiles."""
     r = _rng(count + 77)
     k, seg = 192, 4096
     n = 3 * seg
