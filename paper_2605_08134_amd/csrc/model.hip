@@ -27,8 +27,11 @@ __global__ void __launch_bounds__(256) gather_rows_kernel(const uint4* __restric
     const bool ok = id >= 0 && id < n_src;
     const uint4* s = src + (long)(ok ? id : 0) * row_vec;
     uint4* d = dst + (long)r * row_vec;
-    const uint4 zero = {0u, 0u, 0u, 0u};
-    for (int c = threadIdx.x; c < row_vec; c += 256) d[c] = ok ? s[c] : zero;
+    for (int c = threadIdx.x; c < row_vec; c += 256) {
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (ok) v = s[c];
+      d[c] = v;
+    }
   }
 }
 
